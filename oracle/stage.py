@@ -5,8 +5,8 @@ TEST INFRASTRUCTURE ONLY.  Only tests, the smoke check and the benchmark's cpu_b
 this; it shares no code with the HIP library and is not tuned.
 
 What the paper fixes: the stage's cost is t = y * l * tau(b) and a pipeline's step takes about
-m * max t (Sec. 4.2, time cost model), with l layers and m micro-batches assigned per GPU (Sec. 4.1,
-Eq. 1), on models of the LLaMA-2 architecture with context 4K and micro-batch 1 (Sec. 7.1).  The paper
+m * max t (Sec. 4.2, time cost model), with l layers and m micro-batches assigned per GPU (Sec. 4.2,
+Eq. 1; Table 1 of notations), on models of the LLaMA-2 architecture with context 4K and micro-batch 1 (Sec. 7.1).  The paper
 does not write the layer's arithmetic out; the definitions below are the textbook ones of that
 architecture (pre-norm residual block, RMSNorm, rotary position embedding with half-split pairing,
 causal softmax attention with grouped KV heads, SwiGLU feed-forward, no biases).  The method is exact

@@ -1,0 +1,5 @@
+"""MI355X-native decoder-stage forward/backward: the per-GPU compute of a hybrid-parallel training step
+with a run-time layer count and micro-batch count.  Thin ctypes binding over libmls.so (include/mls.h)."""
+from .binding import (  # noqa: F401
+    MlsError, MlsConfig, Stage, gemm, lib, lib_path, P_NAMES, T_IDS, MLS_BF16, MLS_FP32,
+)

@@ -1,0 +1,168 @@
+"""ctypes binding of the C ABI in include/mls.h: argument marshalling only.
+
+PyTorch appears here for device memory and the stream handle; every step of the path runs in the HIP
+kernels of libmls.so.  There is no fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+MLS_BF16, MLS_FP32 = 0, 1
+P_NAMES = {"gamma1": 0, "w_qkv": 1, "w_o": 2, "gamma2": 3, "w_gu": 4, "w_d": 5}
+T_IDS = {"x": 0, "a": 1, "qkv": 2, "o": 3, "h": 4, "b": 5, "gu": 6, "z": 7, "lse": 8,
+         "dy": 16, "dgu": 17, "dh": 18, "dqkv": 19}
+
+
+class MlsError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"mls error {code}: {msg}")
+        self.code = code
+
+
+class MlsConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("seq", C.c_int32), ("micro_batch", C.c_int32), ("max_layers", C.c_int32),
+                ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
+
+
+def lib_path():
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmls.so")
+
+
+_lib = None
+
+
+def lib():
+    """Load libmls.so (built in-tree by `python -m paper_2410_13333_amd.build`)."""
+    global _lib
+    if _lib is None:
+        p = lib_path()
+        if not os.path.exists(p):
+            raise ImportError(f"{p} is missing: build it with `python -m paper_2410_13333_amd.build`")
+        L = C.CDLL(p)
+        vp, i32, i64, u64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_size_t
+        L.mls_stage_init.argtypes = [C.POINTER(MlsConfig), u64, vp, C.POINTER(vp)]
+        L.mls_stage_forward.argtypes = [vp, vp, i32, vp]
+        L.mls_stage_backward.argtypes = [vp, vp, vp, i32, vp]
+        L.mls_stage_free.argtypes = [vp]
+        L.mls_stage_free.restype = None
+        L.mls_stage_grad_elems.argtypes = [vp]
+        L.mls_stage_grad_elems.restype = sz
+        L.mls_stage_param_layout.argtypes = [vp, i32, i32, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.mls_stage_get_params.argtypes = [vp, vp]
+        L.mls_stage_set_params.argtypes = [vp, vp]
+        L.mls_stage_inflight.argtypes = [vp]
+        L.mls_stage_reset.argtypes = [vp]
+        L.mls_stage_debug_read.argtypes = [vp, i32, i32, i32, vp]
+        L.mls_gemm.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.mls_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise MlsError(rc, lib().mls_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _torch_dtype(dtype):
+    import torch
+    return torch.bfloat16 if dtype == MLS_BF16 else torch.float32
+
+
+class Stage:
+    """One GPU's pipeline stage.  Tensors are torch CUDA tensors used as plain device buffers."""
+
+    def __init__(self, hidden, n_q_heads, n_kv_heads, head_dim, ffn, seq, micro_batch, max_layers, max_inflight,
+                 rms_eps=1e-5, rope_base=10000.0, dtype="bf16", seed=0, stream=None):
+        import torch
+        self.cfg = MlsConfig(hidden, n_q_heads, n_kv_heads, head_dim, ffn, seq, micro_batch, max_layers, max_inflight,
+                             rms_eps, rope_base, MLS_BF16 if dtype == "bf16" else MLS_FP32)
+        self.dtype = self.cfg.dtype
+        self.tdtype = _torch_dtype(self.dtype)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self._h = C.c_void_p(0)
+        _check(lib().mls_stage_init(C.byref(self.cfg), seed, C.c_void_p(self.stream.cuda_stream), C.byref(self._h)))
+
+    @classmethod
+    def from_shape(cls, sh, seed=0, max_layers=None, max_inflight=None, stream=None):
+        """sh: any object with the StageShape fields (hidden, n_q_heads, ..., layers, microbatches, dtype)."""
+        return cls(sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, sh.seq, sh.micro_batch,
+                   sh.layers if max_layers is None else max_layers,
+                   sh.microbatches if max_inflight is None else max_inflight,
+                   sh.rms_eps, sh.rope_base, sh.dtype, seed, stream)
+
+    # ---- hot path
+    def forward(self, x, k_layers, y):
+        _check(lib().mls_stage_forward(self._h, _ptr(x), k_layers, _ptr(y)))
+
+    def backward(self, dy, grads, n_microbatches, dx):
+        _check(lib().mls_stage_backward(self._h, _ptr(dy), _ptr(grads), n_microbatches, _ptr(dx)))
+
+    # ---- support
+    @property
+    def grad_elems(self):
+        return lib().mls_stage_grad_elems(self._h)
+
+    @property
+    def inflight(self):
+        return lib().mls_stage_inflight(self._h)
+
+    def reset(self):
+        _check(lib().mls_stage_reset(self._h))
+
+    def param_layout(self, layer, which):
+        off, r, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        which = P_NAMES[which] if isinstance(which, str) else which
+        _check(lib().mls_stage_param_layout(self._h, layer, which, C.byref(off), C.byref(r), C.byref(c)))
+        return off.value, r.value, c.value
+
+    def get_params(self):
+        import torch
+        out = torch.empty(self.grad_elems, dtype=self.tdtype, device="cuda")
+        _check(lib().mls_stage_get_params(self._h, _ptr(out)))
+        return out
+
+    def set_params(self, src):
+        assert src.is_cuda and src.dtype == self.tdtype and src.numel() == self.grad_elems and src.is_contiguous()
+        _check(lib().mls_stage_set_params(self._h, _ptr(src)))
+
+    def debug_read(self, name, layer=0, slot=0):
+        import torch
+        c = self.cfg
+        T, qd, kvd = c.seq * c.micro_batch, c.n_q_heads * c.head_dim, c.n_kv_heads * c.head_dim
+        shapes = {"x": (T, c.hidden), "a": (T, c.hidden), "qkv": (T, qd + 2 * kvd), "o": (T, qd), "h": (T, c.hidden),
+                  "b": (T, c.hidden), "gu": (T, 2 * c.ffn), "z": (T, c.ffn), "lse": (c.micro_batch, c.n_q_heads, c.seq),
+                  "dy": (T, c.hidden), "dgu": (T, 2 * c.ffn), "dh": (T, c.hidden), "dqkv": (T, qd + 2 * kvd)}
+        out = torch.empty(shapes[name], dtype=torch.float32 if name == "lse" else self.tdtype, device="cuda")
+        _check(lib().mls_stage_debug_read(self._h, T_IDS[name], layer, slot, _ptr(out)))
+        return out
+
+    def close(self):
+        if self._h:
+            lib().mls_stage_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gemm(mode, a, b, c, r=None, stream=None):
+    """Stand-alone call of the stage's contraction kernel; shapes as documented at mls_gemm."""
+    import torch
+    dtype = MLS_BF16 if a.dtype == torch.bfloat16 else MLS_FP32
+    if mode == 0:
+        (M, K), N = a.shape, b.shape[1]
+    elif mode == 1:
+        (M, K), N = a.shape, b.shape[0]
+    else:
+        (K, M), N = a.shape, b.shape[1]
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(lib().mls_gemm(dtype, mode, _ptr(a), _ptr(b), _ptr(c), _ptr(r), M, N, K, C.c_void_p(st.cuda_stream)))

@@ -1,0 +1,472 @@
+// Causal grouped-query attention for bf16 storage on the gfx950 matrix cores: forward with online softmax,
+// backward as two kernels (dQ; dK and dV) that recompute the probabilities from the saved log-sum-exp.
+// Nothing of size S x S is ever written; no float atomics, so results are bitwise reproducible.
+//
+// Register-resident probabilities.  v_mfma_f32_32x32x16_bf16 leaves element (g*4+r) of lane l at
+// [row (l/32)*4 + 8g + r][col l%32] of the 32x32 result and expects the B operand as "lane l holds column
+// l%32, eight k-values".  All score-like products are therefore computed TRANSPOSED so that the softmax row
+// index is the lane's column: a lane then owns all the probabilities of its row that it computed, can turn
+// them into a B operand of the next product without leaving its registers, and keeps the running row
+// maximum / sum as plain scalars.  The contraction index of that next product is permuted (k-values
+// 4g..4g+3 and 8+4g..8+4g+3 per 16-step), which is free because the A operand is fetched with the same
+// permutation by ds_read_b64_tr_b16 out of a tile stored [kv][d] just as it lies in memory.
+//
+// LDS tiles are 64 rows x D columns, unpadded, with an XOR swizzle of the 16-byte chunks that makes both
+// access patterns bank-conflict free: ds_read_b128 of 16 consecutive rows at one column chunk, and the
+// transposing 8-byte reads of 4 consecutive rows x 64 bytes.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr int AT_THREADS = 256;
+constexpr int TR = 64;  // rows of an LDS tile
+constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+// element offset of (row, col) inside a swizzled 64 x D tile
+template <int D>
+__device__ __forceinline__ int toff(int row, int col) {
+  if (D == 128) {
+    const int sw = ((row & 3) << 2) | ((row >> 2) & 3);
+    return row * 128 + ((((col >> 3) ^ sw)) << 3) + (col & 7);
+  } else {
+    const int line = row >> 1;
+    const int sw = ((line & 1) << 2) | ((line >> 1) & 3);
+    return line * 128 + (((((row & 1) << 3) | (col >> 3)) ^ sw) << 3) + (col & 7);
+  }
+}
+
+template <int D>
+struct Tile {
+  static constexpr int CHUNKS = TR * D / 8 / AT_THREADS;  // 16-byte chunks per thread
+  // rows [row0, row0+64) x cols [col0, col0+D) of a row-major matrix; rows >= nrows read as zero
+  static __device__ __forceinline__ void gload(const bf16_t* __restrict__ g, int64_t ld, int row0, int col0, int nrows,
+                                               uint4 (&r)[CHUNKS]) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; i++) {
+      const int id = threadIdx.x + i * AT_THREADS;
+      const int rr = id / (D / 8), cc = (id % (D / 8)) * 8;
+      if (row0 + rr < nrows)
+        r[i] = *reinterpret_cast<const uint4*>(g + int64_t(row0 + rr) * ld + col0 + cc);
+      else
+        r[i] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  static __device__ __forceinline__ void lstore(bf16_t* t, const uint4 (&r)[CHUNKS]) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; i++) {
+      const int id = threadIdx.x + i * AT_THREADS;
+      *reinterpret_cast<uint4*>(t + toff<D>(id / (D / 8), (id % (D / 8)) * 8)) = r[i];
+    }
+  }
+  // A operand, rows = tile rows rt*32 .. +31, k = tile columns kk*16 .. +15
+  static __device__ __forceinline__ bf16x8 frag_rows(const bf16_t* t, int rt, int kk, int lane) {
+    const uint4 v = *reinterpret_cast<const uint4*>(t + toff<D>(rt * 32 + (lane & 31), kk * 16 + (lane >> 5) * 8));
+    return __builtin_bit_cast(bf16x8, v);
+  }
+  // A operand, rows = tile COLUMNS ct*32 .. +31, k = tile rows of the 16-step `ks` in the permuted order
+  // that matches a B operand built from accumulator registers: k-values 4g..4g+3 then 8+4g..8+4g+3, g = lane/32.
+  static __device__ __forceinline__ bf16x8 frag_cols(const bf16_t* t, int ct, int ks, int lane) {
+    const int row = ks * 16 + (lane >> 5) * 4 + ((lane & 15) >> 2);
+    const int col = ct * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLS_LDS s16x4*)(t + toff<D>(row, col)));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLS_LDS s16x4*)(t + toff<D>(row + 8, col)));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+// B operand straight from global memory: column l%32 = matrix row row0 + l%32, k = matrix columns kk*16 + (l/32)*8 ..
+__device__ __forceinline__ bf16x8 gfrag(const bf16_t* __restrict__ g, int64_t ld, int row, int col, bool valid) {
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (valid) v = *reinterpret_cast<const uint4*>(g + int64_t(row) * ld + col);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// two accumulator groups (2s, 2s+1) of a 32x32 result -> B operand of the next product
+__device__ __forceinline__ bf16x8 acc_to_b(const f32x16& a, int s) {
+  uint4 v;
+  v.x = pack_bf16x2(a[8 * s + 0], a[8 * s + 1]);
+  v.y = pack_bf16x2(a[8 * s + 2], a[8 * s + 3]);
+  v.z = pack_bf16x2(a[8 * s + 4], a[8 * s + 5]);
+  v.w = pack_bf16x2(a[8 * s + 6], a[8 * s + 7]);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int e = 0; e < 16; e++) z[e] = 0.f;
+  return z;
+}
+
+// store a transposed 32x32 result (col l%32 = token, rows = feature index) as bf16: 4 consecutive features = 8 bytes
+__device__ __forceinline__ void store_t(bf16_t* __restrict__ out, int64_t ld, int token, int col0, const f32x16& a,
+                                        float mul, int lane, bool valid) {
+  if (!valid) return;
+#pragma unroll
+  for (int g = 0; g < 4; g++) {
+    uint2 v;
+    v.x = pack_bf16x2(a[g * 4 + 0] * mul, a[g * 4 + 1] * mul);
+    v.y = pack_bf16x2(a[g * 4 + 2] * mul, a[g * 4 + 3] * mul);
+    *reinterpret_cast<uint2*>(out + int64_t(token) * ld + col0 + (lane >> 5) * 4 + 8 * g) = v;
+  }
+}
+
+// ================================================================ forward
+// grid (q blocks of 128, n_q, b); wave w owns query rows q0 + 32w .. +31; loops over KV blocks of 64.
+template <int D>
+__global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+                                                              float* __restrict__ lse, int S, int nq, int nkv) {
+  using TL = Tile<D>;
+  constexpr int KD = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];  // [buffer][K|V]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qb = gridDim.x - 1 - blockIdx.x;  // longest rows first
+  const int hq = blockIdx.y, bi = blockIdx.z, hk = hq / (nq / nkv);
+  const int64_t ld = int64_t(nq + 2 * nkv) * D;
+  const bf16_t* base = qkv + int64_t(bi) * S * ld;
+  const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
+  const float sc = rsqrtf((float)D) * LOG2E;
+
+  bf16x8 qf[KD];
+#pragma unroll
+  for (int kk = 0; kk < KD; kk++) qf[kk] = gfrag(base, ld, qi, hq * D + kk * 16 + (lane >> 5) * 8, qi < S);
+
+  f32x16 acc[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++) acc[t] = zero16();
+  float m = -INFINITY, l = 0.f;
+
+  const int kv_end = min(S, q0 + 128);
+  const int nblk = (kv_end + TR - 1) / TR;
+  uint4 rk[TL::CHUNKS], rv[TL::CHUNKS];
+  TL::gload(base, ld, 0, (nq + hk) * D, S, rk);
+  TL::gload(base, ld, 0, (nq + nkv + hk) * D, S, rv);
+  TL::lstore(lds[0][0], rk);
+  TL::lstore(lds[0][1], rv);
+  __syncthreads();
+  for (int blk = 0; blk < nblk; blk++) {
+    const int cur = blk & 1, j0 = blk * TR;
+    const bool more = blk + 1 < nblk;
+    if (more) {
+      TL::gload(base, ld, j0 + TR, (nq + hk) * D, S, rk);
+      TL::gload(base, ld, j0 + TR, (nq + nkv + hk) * D, S, rv);
+    }
+    if (j0 <= qw + 31) {  // wave-uniform: some (i, j) pair of this wave is unmasked
+      const bf16_t* ks = lds[cur][0];
+      const bf16_t* vs = lds[cur][1];
+      f32x16 st[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++) {
+        st[jt] = zero16();
+#pragma unroll
+        for (int kk = 0; kk < KD; kk++)
+          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ks, jt, kk, lane), qf[kk], st[jt], 0, 0, 0);
+      }
+      const bool diag = j0 + TR - 1 > qw;  // some pair may be masked
+      float mx = -INFINITY;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+          float t = st[jt][e] * sc;
+          if (diag && j > qi) t = -INFINITY;
+          st[jt][e] = t;
+          mx = fmaxf(mx, t);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m, mx);  // finite: block 0 always holds j = 0 <= i
+      const float corr = __builtin_amdgcn_exp2f(m - mn);
+      float ps = 0.f;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const float p = __builtin_amdgcn_exp2f(st[jt][e] - mn);
+          st[jt][e] = p;
+          ps += p;
+        }
+      l = l * corr + ps;
+      m = mn;
+#pragma unroll
+      for (int t = 0; t < DT; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[t][e] *= corr;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+          const bf16x8 pf = acc_to_b(st[jt], s);
+#pragma unroll
+          for (int t = 0; t < DT; t++)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(vs, t, jt * 2 + s, lane), pf, acc[t], 0, 0, 0);
+        }
+    }
+    if (more) {
+      TL::lstore(lds[cur ^ 1][0], rk);
+      TL::lstore(lds[cur ^ 1][1], rv);
+    }
+    __syncthreads();
+  }
+  l += __shfl_xor(l, 32, 64);
+  const float inv = 1.f / l;
+  bf16_t* ob = o + int64_t(bi) * S * (int64_t(nq) * D);
+#pragma unroll
+  for (int t = 0; t < DT; t++) store_t(ob, int64_t(nq) * D, qi, hq * D + t * 32, acc[t], inv, lane, qi < S);
+  if (lane < 32 && qi < S) lse[(int64_t(bi) * nq + hq) * S + qi] = (m + __builtin_amdgcn_logf(l)) * LN2;
+}
+
+// ================================================================ backward: dQ
+// Same decomposition as the forward.  Per KV block: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - delta),
+// dQ^T += K^T dS^T.
+template <int D>
+__global__ __launch_bounds__(AT_THREADS) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
+                                                             const bf16_t* __restrict__ d_o,
+                                                             const float* __restrict__ lse,
+                                                             const float* __restrict__ delta,
+                                                             bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
+  using TL = Tile<D>;
+  constexpr int KD = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int hq = blockIdx.y, bi = blockIdx.z, hk = hq / (nq / nkv);
+  const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
+  const bf16_t* base = qkv + int64_t(bi) * S * ld;
+  const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
+  const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
+  const float scale = rsqrtf((float)D), sc = scale * LOG2E;
+
+  bf16x8 qf[KD], dof[KD];
+#pragma unroll
+  for (int kk = 0; kk < KD; kk++) {
+    qf[kk] = gfrag(base, ld, qi, hq * D + kk * 16 + (lane >> 5) * 8, qi < S);
+    dof[kk] = gfrag(dob, ldo, qi, hq * D + kk * 16 + (lane >> 5) * 8, qi < S);
+  }
+  const int64_t si = (int64_t(bi) * nq + hq) * S + qi;
+  const float L2 = qi < S ? lse[si] * LOG2E : 0.f;
+  const float dl = qi < S ? delta[si] : 0.f;
+
+  f32x16 acc[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++) acc[t] = zero16();
+
+  const int kv_end = min(S, q0 + 128);
+  const int nblk = (kv_end + TR - 1) / TR;
+  uint4 rk[TL::CHUNKS], rv[TL::CHUNKS];
+  TL::gload(base, ld, 0, (nq + hk) * D, S, rk);
+  TL::gload(base, ld, 0, (nq + nkv + hk) * D, S, rv);
+  TL::lstore(lds[0][0], rk);
+  TL::lstore(lds[0][1], rv);
+  __syncthreads();
+  for (int blk = 0; blk < nblk; blk++) {
+    const int cur = blk & 1, j0 = blk * TR;
+    const bool more = blk + 1 < nblk;
+    if (more) {
+      TL::gload(base, ld, j0 + TR, (nq + hk) * D, S, rk);
+      TL::gload(base, ld, j0 + TR, (nq + nkv + hk) * D, S, rv);
+    }
+    if (j0 <= qw + 31) {
+      const bf16_t* ks = lds[cur][0];
+      const bf16_t* vs = lds[cur][1];
+      f32x16 st[2], dp[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++) {
+        st[jt] = zero16();
+        dp[jt] = zero16();
+#pragma unroll
+        for (int kk = 0; kk < KD; kk++) {
+          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ks, jt, kk, lane), qf[kk], st[jt], 0, 0, 0);
+          dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(vs, jt, kk, lane), dof[kk], dp[jt], 0, 0, 0);
+        }
+      }
+      const bool diag = j0 + TR - 1 > qw;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+          float p = __builtin_amdgcn_exp2f(st[jt][e] * sc - L2);
+          if (diag && j > qi) p = 0.f;
+          st[jt][e] = p * (dp[jt][e] - dl);
+        }
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+          const bf16x8 df = acc_to_b(st[jt], s);
+#pragma unroll
+          for (int t = 0; t < DT; t++)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ks, t, jt * 2 + s, lane), df, acc[t], 0, 0, 0);
+        }
+    }
+    if (more) {
+      TL::lstore(lds[cur ^ 1][0], rk);
+      TL::lstore(lds[cur ^ 1][1], rv);
+    }
+    __syncthreads();
+  }
+  bf16_t* out = dqkv + int64_t(bi) * S * ld;
+#pragma unroll
+  for (int t = 0; t < DT; t++) store_t(out, ld, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
+}
+
+// ================================================================ backward: dK, dV
+// grid (kv blocks of 128, n_kv, b); wave w owns key rows j0 + 32w .. +31 and keeps their K and V as B operands.
+// Loops over the query heads of the group and the query blocks of 64 rows at or below the diagonal:
+// S = Q K^T and dP = dO V^T (lane column = key row), dV^T += dO^T P, dK^T += Q^T dS.
+template <int D>
+__global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
+                                                              const bf16_t* __restrict__ d_o,
+                                                              const float* __restrict__ lse,
+                                                              const float* __restrict__ delta,
+                                                              bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
+  using TL = Tile<D>;
+  constexpr int KD = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
+  __shared__ float stat[2][2][TR];                                     // [buffer][lse*log2e | delta]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kb = blockIdx.x, hk = blockIdx.y, bi = blockIdx.z, grp = nq / nkv;
+  const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
+  const bf16_t* base = qkv + int64_t(bi) * S * ld;
+  const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
+  const int j0 = kb * 128, jw = j0 + wave * 32, ji = jw + (lane & 31);
+  const float scale = rsqrtf((float)D), sc = scale * LOG2E;
+
+  bf16x8 kf[KD], vf[KD];
+#pragma unroll
+  for (int kk = 0; kk < KD; kk++) {
+    kf[kk] = gfrag(base, ld, ji, (nq + hk) * D + kk * 16 + (lane >> 5) * 8, ji < S);
+    vf[kk] = gfrag(base, ld, ji, (nq + nkv + hk) * D + kk * 16 + (lane >> 5) * 8, ji < S);
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++) { dk[t] = zero16(); dv[t] = zero16(); }
+
+  const int qb0 = j0 / TR, nqb = (S + TR - 1) / TR - qb0;  // query blocks per head
+  const int niter = nqb > 0 ? nqb * grp : 0;
+  uint4 rq[TL::CHUNKS], rd[TL::CHUNKS];
+  float rs = 0.f;  // threads 0..63: lse*log2e of row tid; threads 64..127: delta of row tid-64
+  auto gl = [&](int it) {
+    const int hq = hk * grp + it / nqb, i0 = (qb0 + it % nqb) * TR;
+    TL::gload(base, ld, i0, hq * D, S, rq);
+    TL::gload(dob, ldo, i0, hq * D, S, rd);
+    if (threadIdx.x < 2 * TR) {
+      const int r = threadIdx.x & (TR - 1);
+      const int64_t si = (int64_t(bi) * nq + hq) * S + i0 + r;
+      rs = 0.f;
+      if (i0 + r < S) rs = threadIdx.x < TR ? lse[si] * LOG2E : delta[si];
+    }
+  };
+  auto ls = [&](int buf) {
+    TL::lstore(lds[buf][0], rq);
+    TL::lstore(lds[buf][1], rd);
+    if (threadIdx.x < 2 * TR) stat[buf][threadIdx.x >> 6][threadIdx.x & (TR - 1)] = rs;
+  };
+  if (niter > 0) {
+    gl(0);
+    ls(0);
+  }
+  __syncthreads();
+  for (int it = 0; it < niter; it++) {
+    const int cur = it & 1, i0 = (qb0 + it % nqb) * TR;
+    const bool more = it + 1 < niter;
+    if (more) gl(it + 1);
+    if (i0 + TR - 1 >= jw) {  // wave-uniform: some query row at or below this wave's first key row
+      const bf16_t* qs = lds[cur][0];
+      const bf16_t* ds_ = lds[cur][1];
+      f32x16 st[2], dp[2];
+#pragma unroll
+      for (int itl = 0; itl < 2; itl++) {
+        st[itl] = zero16();
+        dp[itl] = zero16();
+#pragma unroll
+        for (int kk = 0; kk < KD; kk++) {
+          st[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st[itl], 0, 0, 0);
+          dp[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp[itl], 0, 0, 0);
+        }
+      }
+      const bool diag = i0 < jw + 31;
+#pragma unroll
+      for (int itl = 0; itl < 2; itl++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+          float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
+          if ((diag && i0 + r < ji) || i0 + r >= S) p = 0.f;
+          st[itl][e] = p;
+          dp[itl][e] = p * (dp[itl][e] - stat[cur][1][r]);
+        }
+#pragma unroll
+      for (int itl = 0; itl < 2; itl++)
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+          const bf16x8 pf = acc_to_b(st[itl], s), df = acc_to_b(dp[itl], s);
+#pragma unroll
+          for (int t = 0; t < DT; t++) {
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ds_, t, itl * 2 + s, lane), pf, dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(qs, t, itl * 2 + s, lane), df, dk[t], 0, 0, 0);
+          }
+        }
+    }
+    if (more) ls(cur ^ 1);
+    __syncthreads();
+  }
+  bf16_t* out = dqkv + int64_t(bi) * S * ld;
+#pragma unroll
+  for (int t = 0; t < DT; t++) {
+    store_t(out, ld, ji, (nq + hk) * D + t * 32, dk[t], scale, lane, ji < S);
+    store_t(out, ld, ji, (nq + nkv + hk) * D + t * 32, dv[t], 1.f, lane, ji < S);
+  }
+}
+
+}  // namespace
+
+namespace mls {
+
+hipError_t attn_fwd_bf16(const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
+  if (b == 0 || S == 0) return hipSuccess;
+  dim3 grid((S + 127) / 128, nq, b);
+  if (d == 128)
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (bf16_t*)o, lse, S, nq, nkv);
+  else if (d == 64)
+    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (bf16_t*)o, lse, S, nq, nkv);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t attn_bwd_bf16(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
+                         int b, int S, int nq, int nkv, int d, hipStream_t st) {
+  if (b == 0 || S == 0) return hipSuccess;
+  hipError_t e = attn_delta(DT_BF16, o, d_o, delta, b, S, nq, d, st);
+  if (e != hipSuccess) return e;
+  dim3 gq((S + 127) / 128, nq, b), gk((S + 127) / 128, nkv, b);
+  if (d == 128) {
+    hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
+                       delta, (bf16_t*)dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dkv_kernel<128>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
+                       delta, (bf16_t*)dqkv, S, nq, nkv);
+  } else if (d == 64) {
+    hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
+                       delta, (bf16_t*)dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dkv_kernel<64>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
+                       delta, (bf16_t*)dqkv, S, nq, nkv);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t attn_fwd(int dt, const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
+  return dt == DT_BF16 ? attn_fwd_bf16(qkv, o, lse, b, S, nq, nkv, d, st) : attn_fwd_f32(qkv, o, lse, b, S, nq, nkv, d, st);
+}
+hipError_t attn_bwd(int dt, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
+                    int b, int S, int nq, int nkv, int d, hipStream_t st) {
+  return dt == DT_BF16 ? attn_bwd_bf16(qkv, o, lse, d_o, dqkv, delta, b, S, nq, nkv, d, st)
+                       : attn_bwd_f32(qkv, o, lse, d_o, dqkv, delta, b, S, nq, nkv, d, st);
+}
+
+}  // namespace mls

@@ -1,0 +1,311 @@
+// HBM-bound kernels of the decoder layer: RMSNorm forward/backward (with the residual-gradient add fused),
+// rotary embedding, SwiGLU forward/backward, and the weight generator.  All use 16-byte accesses, fp32
+// arithmetic and wavefront (64-lane) reductions; each tensor is read once and written once.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr int EW_THREADS = 256;
+constexpr int NORM_MAXC = 8;  // 16-byte chunks per thread a row may span: hidden <= 8*8*256 = 16384
+
+// ---------------------------------------------------------------- RMSNorm forward: one workgroup per row
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                                 T* __restrict__ a, float* __restrict__ rstd, int h,
+                                                                 float eps) {
+  __shared__ float red[EW_THREADS / 64];
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * h;
+  const int nchunk = h >> 3;
+  float v[NORM_MAXC][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_MAXC; i++) {
+    const int c = threadIdx.x + i * EW_THREADS;
+    if (c < nchunk) {
+      load8(xr + c * 8, v[i]);
+#pragma unroll
+      for (int e = 0; e < 8; e++) ss += v[i][e] * v[i][e];
+    }
+  }
+  const float r = rsqrtf(block_sum(ss, red) / (float)h + eps);
+  if (threadIdx.x == 0) rstd[row] = r;
+#pragma unroll
+  for (int i = 0; i < NORM_MAXC; i++) {
+    const int c = threadIdx.x + i * EW_THREADS;
+    if (c < nchunk) {
+      float g[8], o[8];
+      load8(gamma + c * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = v[i][e] * r * g[e];
+      store8(a + row * h + c * 8, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- RMSNorm backward
+// Workgroup w handles rows w, w + gridDim.x, ...; it keeps its share of the column sums for dgamma in
+// registers and writes them to partial[w][:], which a second kernel adds up in a fixed order.
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ da, const T* __restrict__ x,
+                                                                 const T* __restrict__ gamma,
+                                                                 const float* __restrict__ rstd,
+                                                                 const T* dres, T* dx,
+                                                                 float* __restrict__ partial, int rows, int h) {
+  __shared__ float red[EW_THREADS / 64];
+  const int nchunk = h >> 3;
+  float g[NORM_MAXC][8], dg[NORM_MAXC][8];
+#pragma unroll
+  for (int i = 0; i < NORM_MAXC; i++) {
+    const int c = threadIdx.x + i * EW_THREADS;
+#pragma unroll
+    for (int e = 0; e < 8; e++) dg[i][e] = 0.f;
+    if (c < nchunk) load8(gamma + c * 8, g[i]);
+  }
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+    const float r = rstd[row];
+    float n[NORM_MAXC][8], dn[NORM_MAXC][8];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < NORM_MAXC; i++) {
+      const int c = threadIdx.x + i * EW_THREADS;
+      if (c < nchunk) {
+        float xv[8], dav[8];
+        load8(x + row * h + c * 8, xv);
+        load8(da + row * h + c * 8, dav);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          n[i][e] = xv[e] * r;
+          dn[i][e] = dav[e] * g[i][e];
+          dg[i][e] += dav[e] * n[i][e];
+          dot += dn[i][e] * n[i][e];
+        }
+      }
+    }
+    const float mean = block_sum(dot, red) / (float)h;
+#pragma unroll
+    for (int i = 0; i < NORM_MAXC; i++) {
+      const int c = threadIdx.x + i * EW_THREADS;
+      if (c < nchunk) {
+        float res[8], o[8];
+        load8(dres + row * h + c * 8, res);
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = res[e] + r * (dn[i][e] - n[i][e] * mean);
+        store8(dx + row * h + c * 8, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NORM_MAXC; i++) {
+    const int c = threadIdx.x + i * EW_THREADS;
+    if (c < nchunk) store8(partial + int64_t(blockIdx.x) * h + c * 8, dg[i]);
+  }
+}
+
+__global__ void colsum_add_kernel(const float* __restrict__ partial, float* __restrict__ out, int nblocks, int h) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= h) return;
+  float s = 0.f;
+  for (int b = 0; b < nblocks; b++) s += partial[int64_t(b) * h + c];
+  out[c] += s;
+}
+
+// ---------------------------------------------------------------- rotary embedding, in place
+// One thread rotates 8 pairs (i .. i+7, i+d/2 .. i+d/2+7) of one head of one token.
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void rope_kernel(T* __restrict__ u, const float* __restrict__ cos_tab,
+                                                          const float* __restrict__ sin_tab, int64_t total, int S,
+                                                          int n_heads, int d, int64_t ld, float sign) {
+  const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+  if (id >= total) return;
+  const int cph = d >> 4;  // chunks of 8 pairs per head
+  const int c = int(id % cph);
+  const int head = int((id / cph) % n_heads);
+  const int64_t t = id / (int64_t(cph) * n_heads);
+  const int pos = int(t % S);
+  T* p = u + t * ld + head * d + c * 8;
+  float a[8], b[8], cs[8], sn[8], oa[8], ob[8];
+  load8(p, a);
+  load8(p + (d >> 1), b);
+  load8(cos_tab + int64_t(pos) * (d >> 1) + c * 8, cs);
+  load8(sin_tab + int64_t(pos) * (d >> 1) + c * 8, sn);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    const float s = sign * sn[e];
+    oa[e] = a[e] * cs[e] - b[e] * s;
+    ob[e] = a[e] * s + b[e] * cs[e];
+  }
+  store8(p, oa);
+  store8(p + (d >> 1), ob);
+}
+
+// ---------------------------------------------------------------- SwiGLU
+__device__ __forceinline__ float sigmoidf_(float g) { return 1.f / (1.f + __expf(-g)); }
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ z,
+                                                                int64_t total, int f) {
+  const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+  if (id >= total) return;
+  const int cpr = f >> 3;
+  const int64_t t = id / cpr;
+  const int c = int(id % cpr);
+  float g[8], u[8], o[8];
+  load8(gu + t * 2 * f + c * 8, g);
+  load8(gu + t * 2 * f + f + c * 8, u);
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] = g[e] * sigmoidf_(g[e]) * u[e];
+  store8(z + t * f + c * 8, o);
+}
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void swiglu_bwd_kernel(const T* __restrict__ dz, const T* __restrict__ gu,
+                                                                T* __restrict__ dgu, int64_t total, int f) {
+  const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+  if (id >= total) return;
+  const int cpr = f >> 3;
+  const int64_t t = id / cpr;
+  const int c = int(id % cpr);
+  float g[8], u[8], d[8], og[8], ou[8];
+  load8(gu + t * 2 * f + c * 8, g);
+  load8(gu + t * 2 * f + f + c * 8, u);
+  load8(dz + t * f + c * 8, d);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    const float s = sigmoidf_(g[e]);
+    og[e] = d[e] * u[e] * s * (1.f + g[e] * (1.f - s));
+    ou[e] = d[e] * g[e] * s;
+  }
+  store8(dgu + t * 2 * f + c * 8, og);
+  store8(dgu + t * 2 * f + f + c * 8, ou);
+}
+
+// ---------------------------------------------------------------- weight generator (counter-based, fp64 Box-Muller)
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+// fp64 -> bf16 bits, one round-to-nearest-even (normal range)
+__device__ __forceinline__ uint16_t f64_to_bf16_bits(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t sign = uint32_t(u >> 63) << 15;
+  const int exp = int((u >> 52) & 0x7ff);
+  if (exp == 0) return (uint16_t)sign;
+  const uint64_t man = u & ((1ull << 52) - 1);
+  uint32_t keep = (uint32_t(exp - 1023 + 127) << 7) | uint32_t(man >> 45);
+  const uint64_t rem = man & ((1ull << 45) - 1), half = 1ull << 44;
+  if (rem > half || (rem == half && (keep & 1))) keep += 1;
+  return (uint16_t)(sign | keep);
+}
+__device__ __forceinline__ void put(bf16_t* p, double v) { *reinterpret_cast<uint16_t*>(p) = f64_to_bf16_bits(v); }
+__device__ __forceinline__ void put(float* p, double v) { *p = (float)v; }
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void fill_normal_kernel(T* __restrict__ out, int64_t n, uint64_t stream,
+                                                                 double scale, double offset) {
+  const int64_t i = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+  if (i >= n) return;
+  const uint64_t c = stream + 2ull * (uint64_t)i;
+  const uint64_t r1 = mix64(c), r2 = mix64(c + 1);
+  const double u1 = ((double)(r1 >> 11) + 1.0) * 0x1p-53;
+  const double u2 = (double)(r2 >> 11) * 0x1p-53;
+  const double z = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+  put(out + i, offset + scale * z);
+}
+
+inline int blocks_for(int64_t n) { return int((n + EW_THREADS - 1) / EW_THREADS); }
+
+}  // namespace
+
+namespace mls {
+
+hipError_t rmsnorm_fwd(int dt, const void* x, const void* gamma, void* a, float* r, int T, int h, float eps,
+                       hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(rmsnorm_fwd_kernel<bf16_t>, dim3(T), dim3(EW_THREADS), 0, st, (const bf16_t*)x,
+                       (const bf16_t*)gamma, (bf16_t*)a, r, h, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_fwd_kernel<float>, dim3(T), dim3(EW_THREADS), 0, st, (const float*)x,
+                       (const float*)gamma, (float*)a, r, h, eps);
+  return hipGetLastError();
+}
+
+int rmsnorm_bwd_blocks(int T) { return T < 1024 ? (T > 0 ? T : 1) : 1024; }
+
+hipError_t rmsnorm_bwd(int dt, const void* da, const void* x, const void* gamma, const float* r, const void* dres,
+                       void* dx, float* dgamma, float* partial, int T, int h, hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  const int nb = rmsnorm_bwd_blocks(T);
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(rmsnorm_bwd_kernel<bf16_t>, dim3(nb), dim3(EW_THREADS), 0, st, (const bf16_t*)da,
+                       (const bf16_t*)x, (const bf16_t*)gamma, r, (const bf16_t*)dres, (bf16_t*)dx, partial, T, h);
+  else
+    hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nb), dim3(EW_THREADS), 0, st, (const float*)da, (const float*)x,
+                       (const float*)gamma, r, (const float*)dres, (float*)dx, partial, T, h);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 255) / 256), dim3(256), 0, st, partial, dgamma, nb, h);
+  return hipGetLastError();
+}
+
+hipError_t rope_inplace(int dt, void* u, const float* cos_tab, const float* sin_tab, int T, int S, int n_heads, int d,
+                        int64_t ld, float sign, hipStream_t st) {
+  const int64_t total = int64_t(T) * n_heads * (d >> 4);
+  if (total == 0) return hipSuccess;
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (bf16_t*)u, cos_tab,
+                       sin_tab, total, S, n_heads, d, ld, sign);
+  else
+    hipLaunchKernelGGL(rope_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (float*)u, cos_tab,
+                       sin_tab, total, S, n_heads, d, ld, sign);
+  return hipGetLastError();
+}
+
+hipError_t swiglu_fwd(int dt, const void* gu, void* z, int T, int f, hipStream_t st) {
+  const int64_t total = int64_t(T) * (f >> 3);
+  if (total == 0) return hipSuccess;
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)gu,
+                       (bf16_t*)z, total, f);
+  else
+    hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const float*)gu,
+                       (float*)z, total, f);
+  return hipGetLastError();
+}
+
+hipError_t swiglu_bwd(int dt, const void* dz, const void* gu, void* dgu, int T, int f, hipStream_t st) {
+  const int64_t total = int64_t(T) * (f >> 3);
+  if (total == 0) return hipSuccess;
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)dz,
+                       (const bf16_t*)gu, (bf16_t*)dgu, total, f);
+  else
+    hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const float*)dz,
+                       (const float*)gu, (float*)dgu, total, f);
+  return hipGetLastError();
+}
+
+hipError_t fill_normal(int dt, void* out, int64_t n, uint64_t seed, uint32_t tensor, uint32_t layer, double scale,
+                       double offset, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  auto mixh = [](uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  };
+  const uint64_t stream = mixh(mixh(seed) ^ ((uint64_t(tensor) << 32) | layer));
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(fill_normal_kernel<bf16_t>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (bf16_t*)out, n,
+                       stream, scale, offset);
+  else
+    hipLaunchKernelGGL(fill_normal_kernel<float>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (float*)out, n, stream,
+                       scale, offset);
+  return hipGetLastError();
+}
+
+}  // namespace mls

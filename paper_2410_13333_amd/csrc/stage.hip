@@ -1,0 +1,415 @@
+// Host side of the decoder-stage library: the handle, the activation stash, the fixed kernel sequence of a
+// layer's forward and backward, and the C ABI declared in include/mls.h.  No kernel lives here.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/mls.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+int fail_hip(hipError_t e, const char* what) {
+  return fail(e == hipErrorOutOfMemory ? MLS_E_NOMEM : MLS_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) return fail_hip(e_, #expr);   \
+  } while (0)
+
+// Byte offsets of one layer's tensors inside one stash entry.
+struct LayerStash {
+  size_t x, a, qkv, o, h, b, gu, z, r1, r2, lse, bytes;
+};
+
+}  // namespace
+
+struct mls_stage {
+  mls_config c;
+  int dt;         // mls::DT_*
+  size_t es;      // bytes per stored element
+  int T, qd, kvd, qkvw;
+  hipStream_t st;
+  size_t layer_params;  // elements per layer
+  size_t off_g1, off_wqkv, off_wo, off_g2, off_wgu, off_wd;
+  char* params = nullptr;  // storage type, public layout
+  float *cos_tab = nullptr, *sin_tab = nullptr;
+  LayerStash ls;
+  char* stash = nullptr;  // [max_inflight][max_layers] LayerStash
+  std::vector<int> slot_k;
+  int head = 0, count = 0;  // FIFO ring over the slots
+  // backward workspace
+  char *g0 = nullptr, *g1 = nullptr, *dz = nullptr, *dgu = nullptr, *dbuf = nullptr, *dh = nullptr, *dc = nullptr,
+       *dqkv = nullptr;
+  float *delta = nullptr, *partial = nullptr;
+  const void* last_dy = nullptr;
+
+  char* slot_layer(int slot, int layer) const {
+    return stash + (size_t(slot) * c.max_layers + layer) * ls.bytes;
+  }
+  char* param(int layer, size_t off) const { return params + (size_t(layer) * layer_params + off) * es; }
+};
+
+namespace {
+
+size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+hipError_t gemm(const mls_stage* s, int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
+                int64_t lda, int64_t ldb, int64_t ldc) {
+  return s->dt == mls::DT_BF16 ? mls::gemm_bf16(mode, A, B, C, R, M, N, K, lda, ldb, ldc, s->st)
+                               : mls::gemm_f32(mode, A, B, C, R, M, N, K, lda, ldb, ldc, s->st);
+}
+
+int check_config(const mls_config& c) {
+  if (c.dtype != MLS_BF16 && c.dtype != MLS_FP32) return fail(MLS_E_CONFIG, "dtype must be MLS_BF16 or MLS_FP32");
+  if (c.hidden < 8 || c.hidden % 8 || c.hidden > 16384) return fail(MLS_E_CONFIG, "hidden must be a multiple of 8 in [8, 16384]");
+  if (c.ffn < 8 || c.ffn % 8) return fail(MLS_E_CONFIG, "ffn must be a positive multiple of 8");
+  if (c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads)
+    return fail(MLS_E_CONFIG, "n_kv_heads must be positive and divide n_q_heads");
+  if (c.dtype == MLS_BF16 && c.head_dim != 64 && c.head_dim != 128)
+    return fail(MLS_E_CONFIG, "head_dim must be 64 or 128 for bf16 storage");
+  if (c.dtype == MLS_FP32 && (c.head_dim < 16 || c.head_dim > 128 || c.head_dim % 16))
+    return fail(MLS_E_CONFIG, "head_dim must be a multiple of 16 up to 128 for fp32 storage");
+  if (c.seq < 1 || c.micro_batch < 1) return fail(MLS_E_CONFIG, "seq and micro_batch must be positive");
+  if (c.max_layers < 0 || c.max_inflight < 1) return fail(MLS_E_CONFIG, "max_layers >= 0 and max_inflight >= 1 required");
+  if (!(c.rms_eps >= 0.f) || !(c.rope_base > 0.f)) return fail(MLS_E_CONFIG, "rms_eps >= 0 and rope_base > 0 required");
+  const int64_t T = int64_t(c.seq) * c.micro_batch;
+  const int64_t widest = std::max<int64_t>(2 * int64_t(c.ffn), int64_t(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
+  if (T > (1 << 24) || widest > (1 << 24) || T * widest > (int64_t(1) << 40))
+    return fail(MLS_E_CONFIG, "tokens per micro-batch or layer width too large");
+  return MLS_OK;
+}
+
+int init_weights(mls_stage* s, uint64_t seed) {
+  const mls_config& c = s->c;
+  for (int l = 0; l < c.max_layers; l++) {
+    struct { size_t off; int64_t n; uint32_t tid; double scale, offset; } t[6] = {
+        {s->off_g1, c.hidden, MLS_P_GAMMA1, 0.02, 1.0},
+        {s->off_wqkv, int64_t(c.hidden) * s->qkvw, MLS_P_WQKV, 0.02, 0.0},
+        {s->off_wo, int64_t(s->qd) * c.hidden, MLS_P_WO, 0.02, 0.0},
+        {s->off_g2, c.hidden, MLS_P_GAMMA2, 0.02, 1.0},
+        {s->off_wgu, int64_t(c.hidden) * 2 * c.ffn, MLS_P_WGU, 0.02, 0.0},
+        {s->off_wd, int64_t(c.ffn) * c.hidden, MLS_P_WD, 0.02, 0.0}};
+    for (auto& e : t) HIP_TRY(mls::fill_normal(s->dt, s->param(l, e.off), e.n, seed, e.tid, (uint32_t)l, e.scale, e.offset, s->st));
+  }
+  return MLS_OK;
+}
+
+// ---- one decoder layer, forward.  `x` lives in the stash entry already; `out` receives x + attention + MLP.
+int layer_forward(mls_stage* s, int layer, char* e, void* out) {
+  const mls_config& c = s->c;
+  const LayerStash& L = s->ls;
+  const int T = s->T, h = c.hidden, f = c.ffn;
+  HIP_TRY(mls::rmsnorm_fwd(s->dt, e + L.x, s->param(layer, s->off_g1), e + L.a, (float*)(e + L.r1), T, h, c.rms_eps, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->off_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, h, s->qkvw, s->qkvw));
+  HIP_TRY(mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim,
+                            s->qkvw, 1.f, s->st));
+  HIP_TRY(mls::attn_fwd(s->dt, e + L.qkv, e + L.o, (float*)(e + L.lse), c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads,
+                        c.head_dim, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->off_wo), e + L.h, e + L.x, T, h, s->qd, s->qd, h, h));
+  HIP_TRY(mls::rmsnorm_fwd(s->dt, e + L.h, s->param(layer, s->off_g2), e + L.b, (float*)(e + L.r2), T, h, c.rms_eps, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->off_wgu), e + L.gu, nullptr, T, 2 * f, h, h, 2 * f, 2 * f));
+  HIP_TRY(mls::swiglu_fwd(s->dt, e + L.gu, e + L.z, T, f, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->off_wd), out, e + L.h, T, h, f, f, h, h));
+  return MLS_OK;
+}
+
+// ---- one decoder layer, backward.  dy: gradient w.r.t. the layer output; dx receives the gradient w.r.t. its
+// input; g: this layer's slice of the caller's fp32 gradient vector (accumulated into).
+int layer_backward(mls_stage* s, int layer, const char* e, const void* dy, void* dx, float* g) {
+  const mls_config& c = s->c;
+  const LayerStash& L = s->ls;
+  const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, w = s->qkvw;
+  // MLP
+  HIP_TRY(gemm(s, mls::GEMM_NT, dy, s->param(layer, s->off_wd), s->dz, nullptr, T, f, h, h, h, f));
+  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, f, h, h));
+  HIP_TRY(mls::swiglu_bwd(s->dt, s->dz, e + L.gu, s->dgu, T, f, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->off_wgu), s->dbuf, nullptr, T, h, 2 * f, 2 * f, 2 * f, h));
+  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, h, 2 * f, 2 * f));
+  HIP_TRY(mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.h, s->param(layer, s->off_g2), (const float*)(e + L.r2), dy, s->dh,
+                           g + s->off_g2, s->partial, T, h, s->st));
+  // attention
+  HIP_TRY(gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->off_wo), s->dc, nullptr, T, qd, h, h, h, qd));
+  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, qd, h, h));
+  HIP_TRY(mls::attn_bwd(s->dt, e + L.qkv, e + L.o, (const float*)(e + L.lse), s->dc, s->dqkv, s->delta, c.micro_batch,
+                        c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
+  HIP_TRY(mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, w,
+                            -1.f, s->st));
+  HIP_TRY(gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->off_wqkv), s->dbuf, nullptr, T, h, w, w, w, h));
+  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, h, w, w));
+  HIP_TRY(mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.x, s->param(layer, s->off_g1), (const float*)(e + L.r1), s->dh, dx,
+                           g + s->off_g1, s->partial, T, h, s->st));
+  return MLS_OK;
+}
+
+void release(mls_stage* s) {
+  void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
+               s->delta, s->partial};
+  for (void* q : p)
+    if (q) (void)hipFree(q);
+  delete s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mls_last_error(void) { return g_err.c_str(); }
+
+int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_stage** out) {
+  if (!cfg || !out) return fail(MLS_E_NULL, "mls_stage_init: cfg and out must not be null");
+  *out = nullptr;
+  if (int rc = check_config(*cfg)) return rc;
+  mls_stage* s = new (std::nothrow) mls_stage();
+  if (!s) return fail(MLS_E_NOMEM, "host allocation failed");
+  s->c = *cfg;
+  const mls_config& c = s->c;
+  s->dt = c.dtype == MLS_BF16 ? mls::DT_BF16 : mls::DT_FP32;
+  s->es = c.dtype == MLS_BF16 ? 2 : 4;
+  s->T = c.seq * c.micro_batch;
+  s->qd = c.n_q_heads * c.head_dim;
+  s->kvd = c.n_kv_heads * c.head_dim;
+  s->qkvw = s->qd + 2 * s->kvd;
+  s->st = (hipStream_t)hip_stream;
+  const size_t h = c.hidden, f = c.ffn, T = s->T;
+  s->off_g1 = 0;
+  s->off_wqkv = h;
+  s->off_wo = s->off_wqkv + h * s->qkvw;
+  s->off_g2 = s->off_wo + size_t(s->qd) * h;
+  s->off_wgu = s->off_g2 + h;
+  s->off_wd = s->off_wgu + h * 2 * f;
+  s->layer_params = s->off_wd + f * h;
+
+  LayerStash& L = s->ls;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+  L.x = take(T * h * s->es);
+  L.a = take(T * h * s->es);
+  L.qkv = take(T * s->qkvw * s->es);
+  L.o = take(T * s->qd * s->es);
+  L.h = take(T * h * s->es);
+  L.b = take(T * h * s->es);
+  L.gu = take(T * 2 * f * s->es);
+  L.z = take(T * f * s->es);
+  L.r1 = take(T * 4);
+  L.r2 = take(T * 4);
+  L.lse = take(size_t(c.micro_batch) * c.n_q_heads * c.seq * 4);
+  L.bytes = o;
+  s->slot_k.assign(c.max_inflight, 0);
+
+  auto alloc = [&](void** p, size_t bytes) { return hipMalloc(p, bytes ? bytes : 256); };
+  hipError_t e = hipSuccess;
+  const int nb = mls::rmsnorm_bwd_blocks(s->T);
+  if ((e = alloc((void**)&s->params, size_t(c.max_layers) * s->layer_params * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
+      (e = alloc((void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
+      (e = alloc((void**)&s->stash, size_t(c.max_inflight) * c.max_layers * L.bytes)) != hipSuccess ||
+      (e = alloc((void**)&s->g0, T * h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->g1, T * h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dz, T * f * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dgu, T * 2 * f * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dbuf, T * h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dh, T * h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dc, T * s->qd * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dqkv, T * s->qkvw * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4)) != hipSuccess ||
+      (e = alloc((void**)&s->partial, size_t(nb) * h * 4)) != hipSuccess) {
+    release(s);
+    return fail_hip(e, "hipMalloc");
+  }
+
+  // rotary table: angle(p, i) = p * base^(-2i/d), evaluated in fp64 on the host, stored as fp32
+  {
+    const int d2 = c.head_dim / 2;
+    std::vector<float> cs(size_t(c.seq) * d2), sn(cs.size());
+    for (int i = 0; i < d2; i++) {
+      const double theta = std::pow((double)c.rope_base, -2.0 * i / c.head_dim);
+      for (int p = 0; p < c.seq; p++) {
+        cs[size_t(p) * d2 + i] = (float)std::cos(p * theta);
+        sn[size_t(p) * d2 + i] = (float)std::sin(p * theta);
+      }
+    }
+    if ((e = hipMemcpy(s->cos_tab, cs.data(), cs.size() * 4, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(s->sin_tab, sn.data(), sn.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+      release(s);
+      return fail_hip(e, "hipMemcpy(rotary table)");
+    }
+  }
+  if (int rc = init_weights(s, seed)) {
+    release(s);
+    return rc;
+  }
+  if ((e = hipStreamSynchronize(s->st)) != hipSuccess) {
+    release(s);
+    return fail_hip(e, "hipStreamSynchronize");
+  }
+  *out = s;
+  return MLS_OK;
+}
+
+int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y) {
+  if (!s || !x || !y) return fail(MLS_E_NULL, "mls_stage_forward: null argument");
+  if (k_layers < 0 || k_layers > s->c.max_layers) return fail(MLS_E_RANGE, "k_layers outside [0, max_layers]");
+  if (s->count >= s->c.max_inflight) return fail(MLS_E_STASH, "stash full: max_inflight micro-batches already forwarded");
+  const size_t act = size_t(s->T) * s->c.hidden * s->es;
+  const int slot = (s->head + s->count) % s->c.max_inflight;
+  if (k_layers == 0) {
+    HIP_TRY(hipMemcpyAsync(y, x, act, hipMemcpyDeviceToDevice, s->st));
+  } else {
+    HIP_TRY(hipMemcpyAsync(s->slot_layer(slot, 0) + s->ls.x, x, act, hipMemcpyDeviceToDevice, s->st));
+    for (int l = 0; l < k_layers; l++) {
+      void* out = l + 1 < k_layers ? (void*)(s->slot_layer(slot, l + 1) + s->ls.x) : y;
+      if (int rc = layer_forward(s, l, s->slot_layer(slot, l), out)) return rc;
+    }
+  }
+  s->slot_k[slot] = k_layers;
+  s->count++;
+  return MLS_OK;
+}
+
+int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, void* dX) {
+  if (!s) return fail(MLS_E_NULL, "mls_stage_backward: null handle");
+  if (n < 0) return fail(MLS_E_RANGE, "n_microbatches must be >= 0");
+  if (n == 0) return MLS_OK;
+  if (!dY || !dX || !grads) return fail(MLS_E_NULL, "mls_stage_backward: null argument");
+  if (n > s->count) return fail(MLS_E_STASH, "n_microbatches exceeds the stashed micro-batches");
+  const size_t act = size_t(s->T) * s->c.hidden * s->es;
+  for (int i = 0; i < n; i++) {
+    const int slot = s->head;
+    const int k = s->slot_k[slot];
+    const char* dy = (const char*)dY + size_t(i) * act;
+    char* dx = (char*)dX + size_t(i) * act;
+    if (k == 0) {
+      if (dx != dy) HIP_TRY(hipMemcpyAsync(dx, dy, act, hipMemcpyDeviceToDevice, s->st));
+    } else {
+      const void* cur = dy;
+      for (int l = k - 1; l >= 0; l--) {
+        void* out = l == 0 ? (void*)dx : (void*)((l & 1) ? s->g1 : s->g0);
+        s->last_dy = cur;
+        if (int rc = layer_backward(s, l, s->slot_layer(slot, l), cur, out, grads + size_t(l) * s->layer_params)) return rc;
+        cur = out;
+      }
+    }
+    s->head = (s->head + 1) % s->c.max_inflight;
+    s->count--;
+  }
+  return MLS_OK;
+}
+
+void mls_stage_free(mls_stage* s) {
+  if (!s) return;
+  (void)hipStreamSynchronize(s->st);
+  release(s);
+}
+
+size_t mls_stage_grad_elems(const mls_stage* s) { return s ? size_t(s->c.max_layers) * s->layer_params : 0; }
+
+int mls_stage_param_layout(const mls_stage* s, int32_t layer, int32_t which, size_t* offset, size_t* rows, size_t* cols) {
+  if (!s || !offset || !rows || !cols) return fail(MLS_E_NULL, "mls_stage_param_layout: null argument");
+  if (layer < 0 || layer >= s->c.max_layers) return fail(MLS_E_RANGE, "layer out of range");
+  const size_t h = s->c.hidden, f = s->c.ffn;
+  size_t off, r, c;
+  switch (which) {
+    case MLS_P_GAMMA1: off = s->off_g1; r = 1; c = h; break;
+    case MLS_P_WQKV: off = s->off_wqkv; r = h; c = s->qkvw; break;
+    case MLS_P_WO: off = s->off_wo; r = s->qd; c = h; break;
+    case MLS_P_GAMMA2: off = s->off_g2; r = 1; c = h; break;
+    case MLS_P_WGU: off = s->off_wgu; r = h; c = 2 * f; break;
+    case MLS_P_WD: off = s->off_wd; r = f; c = h; break;
+    default: return fail(MLS_E_RANGE, "unknown parameter tensor");
+  }
+  *offset = size_t(layer) * s->layer_params + off;
+  *rows = r;
+  *cols = c;
+  return MLS_OK;
+}
+
+int mls_stage_get_params(mls_stage* s, void* dst) {
+  if (!s || !dst) return fail(MLS_E_NULL, "mls_stage_get_params: null argument");
+  HIP_TRY(hipMemcpyAsync(dst, s->params, mls_stage_grad_elems(s) * s->es, hipMemcpyDeviceToDevice, s->st));
+  HIP_TRY(hipStreamSynchronize(s->st));
+  return MLS_OK;
+}
+
+int mls_stage_set_params(mls_stage* s, const void* src) {
+  if (!s || !src) return fail(MLS_E_NULL, "mls_stage_set_params: null argument");
+  HIP_TRY(hipMemcpyAsync(s->params, src, mls_stage_grad_elems(s) * s->es, hipMemcpyDeviceToDevice, s->st));
+  HIP_TRY(hipStreamSynchronize(s->st));
+  return MLS_OK;
+}
+
+int mls_stage_inflight(const mls_stage* s) { return s ? s->count : fail(MLS_E_NULL, "null handle"); }
+
+int mls_stage_reset(mls_stage* s) {
+  if (!s) return fail(MLS_E_NULL, "null handle");
+  s->head = 0;
+  s->count = 0;
+  return MLS_OK;
+}
+
+int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, void* dst) {
+  if (!s || !dst) return fail(MLS_E_NULL, "mls_stage_debug_read: null argument");
+  const size_t T = s->T, h = s->c.hidden, f = s->c.ffn, es = s->es;
+  const void* src = nullptr;
+  size_t bytes = 0;
+  if (id >= MLS_T_DY) {
+    switch (id) {
+      case MLS_T_DY: src = s->last_dy; bytes = T * h * es; break;
+      case MLS_T_DGU: src = s->dgu; bytes = T * 2 * f * es; break;
+      case MLS_T_DH: src = s->dh; bytes = T * h * es; break;
+      case MLS_T_DQKV: src = s->dqkv; bytes = T * s->qkvw * es; break;
+      default: return fail(MLS_E_RANGE, "unknown tensor id");
+    }
+    if (!src) return fail(MLS_E_RANGE, "no backward has run yet");
+  } else {
+    if (slot < 0 || slot >= s->count) return fail(MLS_E_RANGE, "stash slot out of range");
+    const int phys = (s->head + slot) % s->c.max_inflight;
+    if (layer < 0 || layer >= s->slot_k[phys]) return fail(MLS_E_RANGE, "layer out of range for this stash entry");
+    const char* e = s->slot_layer(phys, layer);
+    const LayerStash& L = s->ls;
+    switch (id) {
+      case MLS_T_X: src = e + L.x; bytes = T * h * es; break;
+      case MLS_T_A: src = e + L.a; bytes = T * h * es; break;
+      case MLS_T_QKV: src = e + L.qkv; bytes = T * s->qkvw * es; break;
+      case MLS_T_O: src = e + L.o; bytes = T * s->qd * es; break;
+      case MLS_T_H: src = e + L.h; bytes = T * h * es; break;
+      case MLS_T_B: src = e + L.b; bytes = T * h * es; break;
+      case MLS_T_GU: src = e + L.gu; bytes = T * 2 * f * es; break;
+      case MLS_T_Z: src = e + L.z; bytes = T * f * es; break;
+      case MLS_T_LSE: src = e + L.lse; bytes = size_t(s->c.micro_batch) * s->c.n_q_heads * s->c.seq * 4; break;
+      default: return fail(MLS_E_RANGE, "unknown tensor id");
+    }
+  }
+  HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s->st));
+  HIP_TRY(hipStreamSynchronize(s->st));
+  return MLS_OK;
+}
+
+int mls_gemm(int32_t dtype, int32_t mode, const void* A, const void* B, void* C, const void* R, int64_t M, int64_t N,
+             int64_t K, void* hip_stream) {
+  if (!A || !B || !C) return fail(MLS_E_NULL, "mls_gemm: null argument");
+  if (dtype != MLS_BF16 && dtype != MLS_FP32) return fail(MLS_E_CONFIG, "mls_gemm: bad dtype");
+  if (mode < 0 || mode > 2) return fail(MLS_E_CONFIG, "mls_gemm: mode must be 0, 1 or 2");
+  if (M < 0 || N < 0 || K < 0 || M % 8 || N % 8 || K % 8 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
+    return fail(MLS_E_CONFIG, "mls_gemm: dimensions must be non-negative multiples of 8 below 2^24");
+  const int64_t lda = mode == mls::GEMM_TN ? M : K;
+  const int64_t ldb = mode == mls::GEMM_NT ? K : N;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = dtype == MLS_BF16 ? mls::gemm_bf16(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, N, st)
+                                   : mls::gemm_f32(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, N, st);
+  if (e != hipSuccess) return fail_hip(e, "mls_gemm launch");
+  return MLS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+"""The stage's contraction kernel on its own, against fp64 matmul of the same bf16 operands."""
+import numpy as np
+import pytest
+
+from tests.helpers import rel_err, to_host64
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(256, 768, 256), (256, 1376, 256), (256, 256, 688), (392, 520, 328), (8, 8, 8), (1024, 2048, 512),
+          (4096, 4096, 1024), (520, 4104, 264)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_bf16_three_modes(M, N, K):
+    import torch
+    import paper_2410_13333_amd as mls
+    g = torch.Generator(device="cpu").manual_seed(M * 7 + N * 3 + K)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    b = torch.randn(K, N, generator=g).to(torch.bfloat16).cuda()
+    r = torch.randn(M, N, generator=g).to(torch.bfloat16).cuda()
+    a64, b64, r64 = to_host64(a), to_host64(b), to_host64(r)
+    c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    mls.gemm(0, a, b, c)
+    assert rel_err(to_host64(c), a64 @ b64) < 4e-3
+    mls.gemm(0, a, b, c, r)
+    assert rel_err(to_host64(c), a64 @ b64 + r64) < 4e-3
+    mls.gemm(1, a, b.t().contiguous(), c)
+    assert rel_err(to_host64(c), a64 @ b64) < 4e-3
+    acc = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    at = a.t().contiguous()
+    mls.gemm(2, at, b, acc)
+    mls.gemm(2, at, b, acc)
+    torch.cuda.synchronize()
+    assert rel_err(to_host64(acc), 0.5 + 2 * (a64 @ b64)) < 1e-5
+
+
+def test_fp32_three_modes():
+    import torch
+    import paper_2410_13333_amd as mls
+    M, N, K = 136, 200, 72
+    g = torch.Generator(device="cpu").manual_seed(5)
+    a, b = torch.randn(M, K, generator=g).cuda(), torch.randn(K, N, generator=g).cuda()
+    ref = to_host64(a) @ to_host64(b)
+    c = torch.empty(M, N, device="cuda")
+    mls.gemm(0, a, b, c)
+    assert rel_err(to_host64(c), ref) < 1e-6
+    mls.gemm(1, a, b.t().contiguous(), c)
+    assert rel_err(to_host64(c), ref) < 1e-6
+    acc = torch.zeros(M, N, device="cuda")
+    mls.gemm(2, a.t().contiguous(), b, acc)
+    assert rel_err(to_host64(acc), ref) < 1e-6

@@ -1,0 +1,176 @@
+"""GPU parity of the HIP decoder stage against the CPU oracle, through the C ABI (ctypes binding).
+
+Tolerances (relative Frobenius error per tensor, fp64 metric):
+  fp32 storage: 1e-4 for every output and gradient (validates the algorithm with no bf16 in the way);
+  bf16 storage: 1e-2 for y, dX and the parameter gradients against the oracle fed the same bf16 inputs;
+  weight-gradient contraction + fp32 accumulation given identical bf16 operands: 1e-4."""
+import numpy as np
+import pytest
+
+import synth
+from tests.helpers import (gpu_step, grad_errors, oracle_step, rel_err, storage_bits, to_device, to_host64)
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.CONFIGS["tiny"]
+# grouped KV heads, ragged everything: seq not a multiple of any tile, ffn = 8*41, 3 layers, 3 micro-batches
+RAGGED = synth.StageShape(hidden=192, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=328, seq=200, micro_batch=2,
+                          layers=3, microbatches=3)
+GQA128 = synth.StageShape(hidden=256, n_q_heads=4, n_kv_heads=1, head_dim=128, ffn=512, seq=328, micro_batch=1,
+                          layers=1, microbatches=2)
+
+
+def _check(sh, ks, tol, interleave=False):
+    ys, dxs, g, st = gpu_step(sh, 1000, 2000, 3000, ks, interleave)
+    rys, rdxs, rg = oracle_step(sh, 1000, 2000, 3000, ks)
+    for mb in range(len(ks)):
+        assert rel_err(ys[mb], rys[mb]) <= tol, ("y", mb, rel_err(ys[mb], rys[mb]))
+        assert rel_err(dxs[mb], rdxs[mb]) <= tol, ("dx", mb, rel_err(dxs[mb], rdxs[mb]))
+    worst, errs = grad_errors(sh, g, rg, max(ks) if ks else 0)
+    assert worst <= tol, sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+    assert st.inflight == 0
+    st.close()
+    return ys, dxs, g
+
+
+def test_weights_match_the_generator_bit_for_bit():
+    import paper_2410_13333_amd as mls
+    for dtype in ("bf16", "fp32"):
+        sh = TINY.with_(dtype=dtype)
+        st = mls.Stage.from_shape(sh, seed=1000)
+        bits, _ = synth.make_params(sh, 1000)
+        assert np.array_equal(storage_bits(st.get_params()), bits)
+        off, r, c = st.param_layout(1, "w_gu")
+        per = synth.layer_param_elems(sh)
+        assert (off, r, c) == (per + 2 * 256 + 256 * 768 + 256 * 256, 256, 1376) and st.grad_elems == 2 * per
+        st.close()
+
+
+def test_tiny_fp32_matches_oracle_1e4():
+    _check(TINY.with_(dtype="fp32"), [2], 1e-4)
+
+
+def test_tiny_bf16_matches_oracle_1e2():
+    _check(TINY, [2], 1e-2)
+
+
+def test_ragged_gqa_fp32_and_bf16_multi_microbatch():
+    _check(RAGGED.with_(dtype="fp32"), [3, 3, 3], 1e-4)
+    _check(RAGGED, [3, 3, 3], 1e-2)
+
+
+def test_head_dim_128_gqa_single_kv_head():
+    _check(GQA128.with_(dtype="fp32"), [1, 1], 1e-4)
+    _check(GQA128, [1, 1], 1e-2)
+
+
+def test_uneven_layer_counts_and_interleaved_order_agree():
+    """Entries forwarded with different layer counts (including zero) may be mixed; one-forward-one-backward
+    order gives the same result as all forwards then one backward, bit for bit."""
+    ks = [2, 0, 1]
+    a = _check(TINY, ks, 1e-2)
+    b = _check(TINY, ks, 1e-2, interleave=True)
+    for u, v in zip(a[0] + a[1], b[0] + b[1]):
+        assert np.array_equal(u, v)
+    assert np.array_equal(a[2], b[2])
+
+
+def test_run_to_run_bitwise_determinism():
+    a = gpu_step(RAGGED, 1000, 2000, 3000, [3, 2])
+    b = gpu_step(RAGGED, 1000, 2000, 3000, [3, 2])
+    for u, v in zip(a[0] + a[1], b[0] + b[1]):
+        assert np.array_equal(u, v)
+    assert np.array_equal(a[2], b[2])
+    a[3].close()
+    b[3].close()
+
+
+def test_gradients_accumulate_and_are_never_zeroed():
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = TINY
+    st = mls.Stage.from_shape(sh, seed=1000, max_inflight=2)
+    x = to_device(synth.make_x(sh, 2000, 0)[0], "bf16")
+    dy = to_device(synth.make_dy(sh, 3000, 0)[0], "bf16")[None]
+    y, dx = torch.empty_like(x), torch.empty_like(dy)
+    g1 = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+    st.forward(x, 2, y)
+    st.backward(dy, g1, 1, dx)
+    g2 = torch.full((st.grad_elems,), 7.0, dtype=torch.float32, device="cuda")
+    st.forward(x, 2, y)
+    st.forward(x, 2, y)
+    st.backward(torch.cat([dy, dy]), g2, 2, torch.empty(2, *x.shape, dtype=x.dtype, device="cuda"))
+    torch.cuda.synchronize()
+    ref = 7.0 + 2.0 * to_host64(g1)
+    assert rel_err(to_host64(g2), ref) < 1e-6
+    st.close()
+
+
+def test_zero_layers_zero_microbatches_and_errors():
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = TINY
+    st = mls.Stage.from_shape(sh, seed=1, max_inflight=2)
+    x = to_device(synth.make_x(sh, 2000, 0)[0], "bf16")
+    y = torch.empty_like(x)
+    g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+    st.backward(None, None, 0, None)                      # n = 0: no-op even with null buffers
+    st.forward(x, 0, y)                                   # k = 0: identity, still one stash entry
+    assert st.inflight == 1
+    dy = to_device(synth.make_dy(sh, 3000, 0)[0], "bf16")[None]
+    dx = torch.empty_like(dy)
+    st.backward(dy, g, 1, dx)
+    torch.cuda.synchronize()
+    assert torch.equal(y, x) and torch.equal(dx, dy) and not g.any()
+    with pytest.raises(mls.MlsError) as e:
+        st.backward(dy, g, 1, dx)                         # nothing stashed
+    assert e.value.code == -4
+    with pytest.raises(mls.MlsError) as e:
+        st.forward(x, 3, y)                               # beyond max_layers
+    assert e.value.code == -3
+    st.forward(x, 1, y)
+    st.forward(x, 1, y)
+    with pytest.raises(mls.MlsError) as e:
+        st.forward(x, 1, y)                               # stash full
+    assert e.value.code == -4
+    with pytest.raises(mls.MlsError) as e:
+        st.forward(None, 1, y)
+    assert e.value.code == -2
+    st.reset()
+    assert st.inflight == 0
+    st.close()
+    with pytest.raises(mls.MlsError) as e:
+        mls.Stage(hidden=100, n_q_heads=4, n_kv_heads=3, head_dim=64, ffn=688, seq=8, micro_batch=1, max_layers=1,
+                  max_inflight=1)
+    assert e.value.code == -1
+
+
+def test_weight_gradient_contraction_given_identical_operands_1e4():
+    """The 1e-4 bar of the fp32-accumulated weight gradients: capture the bf16 operand pairs of every
+    weight-gradient contraction of layer 0 and rebuild sum_mb X^T dY in fp64 from exactly those operands."""
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = RAGGED.with_(layers=1)
+    n = 3
+    st = mls.Stage.from_shape(sh, seed=1000, max_inflight=1)
+    g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+    ref = {k: 0.0 for k in ("w_d", "w_gu", "w_o", "w_qkv")}
+    for mb in range(n):
+        x = to_device(synth.make_x(sh, 2000, mb)[0], "bf16")
+        dy = to_device(synth.make_dy(sh, 3000, mb)[0], "bf16")[None]
+        y, dx = torch.empty_like(x), torch.empty_like(dy)
+        st.forward(x, 1, y)
+        ops = {k: to_host64(st.debug_read(k)) for k in ("z", "b", "o", "a")}
+        st.backward(dy, g, 1, dx)
+        ups = {k: to_host64(st.debug_read(k)) for k in ("dy", "dgu", "dh", "dqkv")}
+        ref["w_d"] = ref["w_d"] + ops["z"].T @ ups["dy"]
+        ref["w_gu"] = ref["w_gu"] + ops["b"].T @ ups["dgu"]
+        ref["w_o"] = ref["w_o"] + ops["o"].T @ ups["dh"]
+        ref["w_qkv"] = ref["w_qkv"] + ops["a"].T @ ups["dqkv"]
+    torch.cuda.synchronize()
+    gh = to_host64(g)
+    for name, r in ref.items():
+        off, rows, cols = st.param_layout(0, name)
+        e = rel_err(gh[off:off + rows * cols].reshape(rows, cols), r)
+        assert e <= 1e-4, (name, e)
+    st.close()
