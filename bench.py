@@ -1,0 +1,128 @@
+#!/usr/bin/env python3
+"""Benchmark of the decoder-stage hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: zero the fp32 gradient buffer,
+M x mls_stage_forward, one mls_stage_backward over the M stashed micro-batches (the 7B-shaped stage:
+4 layers, 4 micro-batches of 4096 tokens).  Prints ONE JSON line.  Inputs are resident in HBM before the
+timed region starts.  Model FLOPs: 3 x (dense GEMMs + causal-halved attention), recompute not credited.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def cpu_baseline(sh):
+    """The CPU oracle as it stands on a bounded sample: ONE layer x ONE micro-batch at the full shape
+    (the work is exactly linear in layers x micro-batches), forward + backward in fp64."""
+    import numpy as np
+    import synth
+    from oracle import stage as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    one = sh.with_(layers=1, microbatches=1)
+    _, p64 = synth.make_params(one, 1001)
+    W = [synth.split_params(one, p64, 0)]
+    _, x = synth.make_x(one, 2001, 0)
+    _, dy = synth.make_dy(one, 3001, 0)
+    t0 = time.perf_counter()
+    y, caches = O.stage_forward(x, W, one)
+    O.stage_backward(dy, W, caches, one)
+    dt = time.perf_counter() - t0
+    flops = one.model_flops_layer_mb()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 layer x 1 micro-batch of the same shape, fwd+bwd, fp64 numpy, {dt:.1f} s",
+            "tokens_per_s": one.tokens / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import synth
+    import paper_2410_13333_amd as mls
+    from tests.helpers import to_device
+
+    sh = synth.CONFIGS[a.workload]
+    K, M = sh.layers, sh.microbatches
+    torch.cuda.set_device(0)
+    st = mls.Stage.from_shape(sh, seed=1001)
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    xs = [to_device(synth.make_x(sh, 2001, mb)[0], sh.dtype) for mb in range(M)]
+    dy = torch.stack([to_device(synth.make_dy(sh, 3001, mb)[0], sh.dtype) for mb in range(M)])
+    ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(M)]
+    dx = torch.empty_like(dy)
+    grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+
+    def step():
+        grads.zero_()
+        for mb in range(M):
+            st.forward(xs[mb], K, ys[mb])
+        st.backward(dy, grads, M, dx)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+
+    # per-kernel-class durations from HIP events on the stage's stream, over the same K-step region again
+    st.timing(True)
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    tm = st.timing_read()
+    st.timing(False)
+    classes = {k: {"ms_per_step": v[0] / a.steps, "launches_per_step": v[1] // a.steps} for k, v in tm.items()}
+
+    flops_step = sh.model_flops_layer_mb() * K * M
+    tflops = flops_step / (ms * 1e-3) / 1e12
+    # dominant kernel: the bf16 MFMA GEMM (12 launches per layer per micro-batch)
+    gemm_ms = sum(tm[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
+    gemm_n = sum(tm[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
+    gemm_flops_launch = 3 * 2 * sh.tokens * sh.matrix_params() / 12.0
+    achieved = gemm_flops_launch / (gemm_ms / gemm_n * 1e-3) / 1e12
+    out = {
+        "metric": "stage fwd+bwd TFLOP/s (bf16)", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}-shaped stage: {K} layers x {M} micro-batches, hidden {sh.hidden}, "
+                               f"{sh.n_q_heads}/{sh.n_kv_heads} heads x {sh.head_dim}, ffn {sh.ffn}, seq {sh.seq}, "
+                               f"micro-batch {sh.micro_batch}", "layers": K, "microbatches": M},
+        "tokens_per_s": M * sh.tokens / (ms * 1e-3),
+        "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "tau_ms_per_layer_microbatch": ms / (K * M),
+        "model_flops_per_step": flops_step,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flops_per_launch": gemm_flops_launch, "avg_launch_ms": gemm_ms / gemm_n},
+        "kernel_classes": classes,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(sh)
+    st.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

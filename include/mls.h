@@ -145,6 +145,17 @@ int mls_stage_reset(mls_stage* s);
  * ids `layer` and `slot` are ignored.  Errors: MLS_E_NULL, MLS_E_RANGE, MLS_E_HIP. */
 int mls_stage_debug_read(mls_stage* s, int32_t tensor_id, int32_t layer, int32_t slot, void* dst);
 
+/* Per-kernel-class timing with HIP events recorded on the stage's stream, for the benchmark's roofline figure.
+ * enable != 0 brackets every kernel launch of forward/backward with a pair of events (no synchronisation unless
+ * more than 4096 launches are pending); enable = 0 stops it.  mls_stage_timing_read synchronises on the last
+ * event, writes the accumulated milliseconds and launch counts per class into two HOST arrays of
+ * MLS_TIMING_CLASSES entries (order: GEMM forward, GEMM data-gradient, GEMM weight-gradient, attention
+ * forward, attention backward, RMSNorm, rotary, SwiGLU) and clears the accumulators.
+ * Errors: MLS_E_NULL, MLS_E_HIP. */
+#define MLS_TIMING_CLASSES 8
+int mls_stage_timing(mls_stage* s, int32_t enable);
+int mls_stage_timing_read(mls_stage* s, double* ms /*host*/, int64_t* launches /*host*/);
+
 /* Stand-alone GEMM entry used by tests and micro-benchmarks of the stage's contraction kernel:
  * mode 0: C[M,N] = A[M,K] * B[K,N] (+ R[M,N] if R != NULL)   forward projections (+ residual)
  * mode 1: C[M,N] = A[M,K] * B[N,K]^T                          data gradients

@@ -54,6 +54,8 @@ def lib():
         L.mls_stage_inflight.argtypes = [vp]
         L.mls_stage_reset.argtypes = [vp]
         L.mls_stage_debug_read.argtypes = [vp, i32, i32, i32, vp]
+        L.mls_stage_timing.argtypes = [vp, i32]
+        L.mls_stage_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.mls_gemm.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp]
         L.mls_last_error.restype = C.c_char_p
         _lib = L
@@ -141,6 +143,18 @@ class Stage:
         out = torch.empty(shapes[name], dtype=torch.float32 if name == "lse" else self.tdtype, device="cuda")
         _check(lib().mls_stage_debug_read(self._h, T_IDS[name], layer, slot, _ptr(out)))
         return out
+
+    TIMING_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "rmsnorm", "rope", "swiglu")
+
+    def timing(self, enable):
+        _check(lib().mls_stage_timing(self._h, 1 if enable else 0))
+
+    def timing_read(self):
+        """{class: (milliseconds, launches)} accumulated since the last read."""
+        n = len(self.TIMING_CLASSES)
+        ms, cnt = (C.c_double * n)(), (C.c_int64 * n)()
+        _check(lib().mls_stage_timing_read(self._h, ms, cnt))
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(self.TIMING_CLASSES)}
 
     def close(self):
         if self._h:

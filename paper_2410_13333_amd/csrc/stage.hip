@@ -28,6 +28,42 @@ int fail_hip(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(e_, #expr);   \
   } while (0)
 
+// Optional per-kernel-class timing with HIP events recorded on the stage's own stream (off by default; the
+// events add no synchronisation unless the pool runs out, which only happens while timing is on).
+enum { CLS_GEMM_NN = 0, CLS_GEMM_NT, CLS_GEMM_TN, CLS_ATTN_FWD, CLS_ATTN_BWD, CLS_NORM, CLS_ROPE, CLS_SWIGLU, CLS_COUNT };
+
+struct Timing {
+  bool on = false;
+  std::vector<hipEvent_t> ev;  // pairs: start, stop
+  std::vector<int> cls;
+  size_t used = 0;
+  double ms[CLS_COUNT] = {};
+  int64_t launches[CLS_COUNT] = {};
+
+  hipError_t flush() {
+    if (used == 0) return hipSuccess;
+    hipError_t e = hipEventSynchronize(ev[2 * used - 1]);
+    if (e != hipSuccess) return e;
+    for (size_t i = 0; i < used; i++) {
+      float t = 0.f;
+      if ((e = hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1])) != hipSuccess) return e;
+      ms[cls[i]] += t;
+      launches[cls[i]]++;
+    }
+    used = 0;
+    return hipSuccess;
+  }
+  hipError_t begin(int c, hipStream_t st) {
+    if (used * 2 == ev.size()) {
+      hipError_t e = flush();
+      if (e != hipSuccess) return e;
+    }
+    cls[used] = c;
+    return hipEventRecord(ev[2 * used], st);
+  }
+  hipError_t end(hipStream_t st) { return hipEventRecord(ev[2 * used++ + 1], st); }
+};
+
 // Byte offsets of one layer's tensors inside one stash entry.
 struct LayerStash {
   size_t x, a, qkv, o, h, b, gu, z, r1, r2, lse, bytes;
@@ -54,6 +90,7 @@ struct mls_stage {
        *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr;
   const void* last_dy = nullptr;
+  Timing tm;
 
   char* slot_layer(int slot, int layer) const {
     return stash + (size_t(slot) * c.max_layers + layer) * ls.bytes;
@@ -64,6 +101,14 @@ struct mls_stage {
 namespace {
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// launch `expr` (a hipError_t expression), bracketed by events of class `c` while timing is on
+#define LAUNCH(c, expr)                                  \
+  do {                                                   \
+    if (s->tm.on) HIP_TRY(s->tm.begin(c, s->st));        \
+    HIP_TRY(expr);                                       \
+    if (s->tm.on) HIP_TRY(s->tm.end(s->st));             \
+  } while (0)
 
 hipError_t gemm(const mls_stage* s, int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
                 int64_t lda, int64_t ldb, int64_t ldc) {
@@ -111,17 +156,17 @@ int layer_forward(mls_stage* s, int layer, char* e, void* out) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn;
-  HIP_TRY(mls::rmsnorm_fwd(s->dt, e + L.x, s->param(layer, s->off_g1), e + L.a, (float*)(e + L.r1), T, h, c.rms_eps, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->off_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, h, s->qkvw, s->qkvw));
-  HIP_TRY(mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim,
+  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.x, s->param(layer, s->off_g1), e + L.a, (float*)(e + L.r1), T, h, c.rms_eps, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->off_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, h, s->qkvw, s->qkvw));
+  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim,
                             s->qkvw, 1.f, s->st));
-  HIP_TRY(mls::attn_fwd(s->dt, e + L.qkv, e + L.o, (float*)(e + L.lse), c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads,
+  LAUNCH(CLS_ATTN_FWD, mls::attn_fwd(s->dt, e + L.qkv, e + L.o, (float*)(e + L.lse), c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads,
                         c.head_dim, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->off_wo), e + L.h, e + L.x, T, h, s->qd, s->qd, h, h));
-  HIP_TRY(mls::rmsnorm_fwd(s->dt, e + L.h, s->param(layer, s->off_g2), e + L.b, (float*)(e + L.r2), T, h, c.rms_eps, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->off_wgu), e + L.gu, nullptr, T, 2 * f, h, h, 2 * f, 2 * f));
-  HIP_TRY(mls::swiglu_fwd(s->dt, e + L.gu, e + L.z, T, f, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->off_wd), out, e + L.h, T, h, f, f, h, h));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->off_wo), e + L.h, e + L.x, T, h, s->qd, s->qd, h, h));
+  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.h, s->param(layer, s->off_g2), e + L.b, (float*)(e + L.r2), T, h, c.rms_eps, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->off_wgu), e + L.gu, nullptr, T, 2 * f, h, h, 2 * f, 2 * f));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, e + L.z, T, f, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->off_wd), out, e + L.h, T, h, f, f, h, h));
   return MLS_OK;
 }
 
@@ -132,23 +177,23 @@ int layer_backward(mls_stage* s, int layer, const char* e, const void* dy, void*
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, w = s->qkvw;
   // MLP
-  HIP_TRY(gemm(s, mls::GEMM_NT, dy, s->param(layer, s->off_wd), s->dz, nullptr, T, f, h, h, h, f));
-  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, f, h, h));
-  HIP_TRY(mls::swiglu_bwd(s->dt, s->dz, e + L.gu, s->dgu, T, f, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->off_wgu), s->dbuf, nullptr, T, h, 2 * f, 2 * f, 2 * f, h));
-  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, h, 2 * f, 2 * f));
-  HIP_TRY(mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.h, s->param(layer, s->off_g2), (const float*)(e + L.r2), dy, s->dh,
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->off_wd), s->dz, nullptr, T, f, h, h, h, f));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, f, h, h));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, e + L.gu, s->dgu, T, f, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->off_wgu), s->dbuf, nullptr, T, h, 2 * f, 2 * f, 2 * f, h));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, h, 2 * f, 2 * f));
+  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.h, s->param(layer, s->off_g2), (const float*)(e + L.r2), dy, s->dh,
                            g + s->off_g2, s->partial, T, h, s->st));
   // attention
-  HIP_TRY(gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->off_wo), s->dc, nullptr, T, qd, h, h, h, qd));
-  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, qd, h, h));
-  HIP_TRY(mls::attn_bwd(s->dt, e + L.qkv, e + L.o, (const float*)(e + L.lse), s->dc, s->dqkv, s->delta, c.micro_batch,
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->off_wo), s->dc, nullptr, T, qd, h, h, h, qd));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, qd, h, h));
+  LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, e + L.o, (const float*)(e + L.lse), s->dc, s->dqkv, s->delta, c.micro_batch,
                         c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
-  HIP_TRY(mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, w,
+  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, w,
                             -1.f, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->off_wqkv), s->dbuf, nullptr, T, h, w, w, w, h));
-  HIP_TRY(gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, h, w, w));
-  HIP_TRY(mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.x, s->param(layer, s->off_g1), (const float*)(e + L.r1), s->dh, dx,
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->off_wqkv), s->dbuf, nullptr, T, h, w, w, w, h));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, h, w, w));
+  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.x, s->param(layer, s->off_g1), (const float*)(e + L.r1), s->dh, dx,
                            g + s->off_g1, s->partial, T, h, s->st));
   return MLS_OK;
 }
@@ -158,6 +203,7 @@ void release(mls_stage* s) {
                s->delta, s->partial};
   for (void* q : p)
     if (q) (void)hipFree(q);
+  for (hipEvent_t e : s->tm.ev) (void)hipEventDestroy(e);
   delete s;
 }
 
@@ -393,6 +439,30 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
   }
   HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s->st));
   HIP_TRY(hipStreamSynchronize(s->st));
+  return MLS_OK;
+}
+
+int mls_stage_timing(mls_stage* s, int32_t enable) {
+  if (!s) return fail(MLS_E_NULL, "null handle");
+  if (enable && s->tm.ev.empty()) {
+    s->tm.ev.resize(2 * 4096);
+    s->tm.cls.resize(4096);
+    for (auto& e : s->tm.ev) HIP_TRY(hipEventCreate(&e));
+  }
+  if (!enable) HIP_TRY(s->tm.flush());
+  s->tm.on = enable != 0;
+  return MLS_OK;
+}
+
+int mls_stage_timing_read(mls_stage* s, double* ms, int64_t* launches) {
+  if (!s || !ms || !launches) return fail(MLS_E_NULL, "mls_stage_timing_read: null argument");
+  HIP_TRY(s->tm.flush());
+  for (int i = 0; i < CLS_COUNT; i++) {
+    ms[i] = s->tm.ms[i];
+    launches[i] = s->tm.launches[i];
+    s->tm.ms[i] = 0;
+    s->tm.launches[i] = 0;
+  }
   return MLS_OK;
 }
 
