@@ -113,7 +113,7 @@ def main():
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "tau_ms_per_layer_microbatch": ms / (K * M),
         "model_flops_per_step": flops_step,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
                      "flops_per_launch": gemm_flops_launch, "avg_launch_ms": gemm_ms / gemm_n},
         "kernel_classes": classes,

@@ -208,6 +208,7 @@ hipError_t gemm_bf16(int mode, const void* A, const void* B, void* C, const void
   const bf16_t* b = static_cast<const bf16_t*>(B);
   const bf16_t* r = static_cast<const bf16_t*>(R);
   if (M == 0 || N == 0) return hipSuccess;
+  if (gemm_bf16_dma_ok(mode, M, N, K, lda, ldb)) return gemm_bf16_dma(mode, A, B, C, R, M, N, K, lda, ldb, ldc, st);
   switch (mode) {
     case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, st);
     case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, st);

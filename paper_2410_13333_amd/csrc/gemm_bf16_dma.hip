@@ -1,0 +1,302 @@
+// bf16 GEMM, main path: tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds), so the
+// main loop holds no staging registers and no LDS stores; out-of-range rows and columns are zero-filled by
+// the buffer range check instead of branches.  Same three modes and epilogues as gemm_bf16.hip.
+//
+// LDS tiles are unpadded (the DMA writes 64 lanes x 16 B contiguously) and XOR-swizzled on the global-address
+// side so that both fragment read patterns are bank-conflict free:
+//   [row][k] tiles (contraction index contiguous in memory), read with ds_read_b128:
+//        16-byte chunk c of row r lives in slot c ^ ((r / rows_per_256B) % chunks_per_row)
+//   [k][col] tiles (contraction index strided in memory), read with ds_read_b64_tr_b16:
+//        16-byte chunk c of k-row r lives in chunk c ^ ((r & 3) << 2)   (moves 64-byte blocks)
+// The pipeline keeps NS tile stages in LDS with ONE workgroup barrier per k-step: the loads of tile kt+NS-1 are
+// issued right after the barrier that publishes tile kt and retires the reads of tile kt-1.
+// The LDS-DMA instructions are inline asm because the compiler would otherwise wait for all of them
+// (vmcnt(0)) before every LDS read; the waits are placed by hand.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+enum { EPI_BF16 = 0, EPI_F32_ACC = 1 };
+
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_byte), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  i32x4 r;
+  r[0] = (int)(uint32_t)a;
+  r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);  // stride 0: raw buffer, byte offsets
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+
+constexpr uint32_t OOB = 0x80000000u;  // beyond any num_records accepted by the launcher
+
+// ---- [row][k] tile: ROWS x BK elements, BK*2 bytes per row
+template <int ROWS, int BK>
+struct RowTile {
+  static constexpr int RB = BK * 2, CPR = RB / 16, RPB = 256 / RB;  // row bytes, chunks per row, rows per 256 B
+  static constexpr int BYTES = ROWS * RB, RPI = 1024 / RB;          // rows per DMA instruction
+  static constexpr int NI = ROWS / RPI / 4;                         // DMA instructions per wave
+  static_assert(RB == 64 || RB == 128, "BK must be 32 or 64");
+  uint32_t goff[NI];  // byte offset of this lane's chunk at k-tile 0 (OOB if the row is out of range)
+  int kcol[NI];       // its first k index inside a tile
+  __device__ __forceinline__ void init(int row0, int nrows, int64_t ld, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NI; i++) {
+      const int r = (wave * NI + i) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ ((r / RPB) % CPR);  // logical chunk stored in this lane's slot
+      kcol[i] = c * 8;
+      goff[i] = row0 + r < nrows ? uint32_t((int64_t(row0 + r) * ld + c * 8) * 2) : OOB;
+    }
+  }
+  // byte offset of DMA instruction i for the tile starting at k0 (columns at or beyond K are out of range)
+  __device__ __forceinline__ uint32_t voff(int i, int k0, int K, int64_t) const {
+    return k0 + kcol[i] < K ? goff[i] + uint32_t(k0) * 2 : OOB;
+  }
+  // MFMA operand: lane l = row rbase + l%32, k = kk*16 + (l/32)*8 .. +7
+  static __device__ __forceinline__ bf16x8 frag(const unsigned char* t, int rbase, int kk, int lane) {
+    const int r = rbase + (lane & 31), c = kk * 2 + (lane >> 5);
+    const uint4 v = *reinterpret_cast<const uint4*>(t + r * RB + ((c ^ ((r / RPB) % CPR)) << 4));
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+// ---- [k][col] tile: BK x COLS elements, COLS*2 bytes per k-row
+template <int COLS, int BK>
+struct ColTile {
+  static constexpr int CB = COLS * 2, CPR = CB / 16;
+  static constexpr int BYTES = BK * CB, RPI = 1024 / CB;
+  static constexpr int NI = BK / RPI / 4;
+  static_assert(CPR >= 16, "tile must be at least 128 columns wide");
+  uint32_t goff[NI];  // byte offset at k-tile 0 (OOB if the column is out of range)
+  __device__ __forceinline__ void init(int col0, int ncols, int64_t ld, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NI; i++) {
+      const int r = (wave * NI + i) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ ((r & 3) << 2);
+      goff[i] = col0 + c * 8 < ncols ? uint32_t((int64_t(r) * ld + col0 + c * 8) * 2) : OOB;
+    }
+  }
+  // k-rows beyond K lie beyond the end of the matrix and are zero-filled by the range check
+  __device__ __forceinline__ uint32_t voff(int i, int k0, int, int64_t ld) const {
+    return goff[i] < OOB ? goff[i] + uint32_t(int64_t(k0) * ld * 2) : OOB;
+  }
+  // MFMA operand: lane l = column cbase + l%32, k = kk*16 + (l/32)*8 .. +7.  A transposing read serves 16
+  // lanes: lane 4r+c passes the address of (k0 + r, col0 + 4c) and receives k0..k0+3 of column col0 + lane%16.
+  static __device__ __forceinline__ bf16x8 frag(const unsigned char* t, int cbase, int kk, int lane) {
+    const int kr = kk * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const int col = cbase + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+    const int sw = (kr & 3) << 2;
+    const unsigned char* p = t + kr * CB + (((col >> 3) ^ sw) << 4) + (col & 7) * 2;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLS_LDS s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLS_LDS s16x4*)(p + 4 * CB));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI>
+__global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                       void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
+                                                       int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
+                                                       uint32_t a_bytes, uint32_t b_bytes, int tiles_m) {
+  using AT_R = RowTile<BM, BK>;
+  using AT_C = ColTile<BM, BK>;
+  using BT_R = RowTile<BN, BK>;
+  using BT_C = ColTile<BN, BK>;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int TM = BM / 64, TN = BN / 64, KS = BK / 16;
+  constexpr int LPT = (ATR ? AT_C::NI : AT_R::NI) + (BTR ? BT_C::NI : BT_R::NI);  // DMA loads per wave per tile
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int nwg = gridDim.x, pid = blockIdx.x;
+  const int xcd = pid & 7, q = nwg >> 3, rem = nwg & 7;
+  const int tile = xcd * q + (xcd < rem ? xcd : rem) + (pid >> 3);
+  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
+
+  const i32x4 ra = make_rsrc(A, a_bytes), rb = make_rsrc(B, b_bytes);
+  AT_R atr;
+  AT_C atc;
+  BT_R btr;
+  BT_C btc;
+  if (ATR) atc.init(m0, M, lda, wave, lane); else atr.init(m0, M, lda, wave, lane);
+  if (BTR) btc.init(n0, N, ldb, wave, lane); else btr.init(n0, N, ldb, wave, lane);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS unsigned char*)smem;
+  const uint32_t a_wave = lds0 + wave * (A_BYTES / 4), b_wave = lds0 + A_BYTES + wave * (B_BYTES / 4);
+  constexpr int NIA = ATR ? AT_C::NI : AT_R::NI, NIB = BTR ? BT_C::NI : BT_R::NI;
+  // DMA instruction d (0 .. LPT-1) of this wave for k-tile kt into `stage`: the first NIA belong to A
+  // (`live` false: the tile does not exist; the load is sent out of range and only zero-fills a dead stage, which
+  // keeps the number of loads per k-step, and with it the vmcnt bookkeeping, constant and the loop branch-free)
+  auto fire = [&](int d, int kt, int stage, bool live) {
+    const int k0 = kt * BK;
+    if (d < NIA) {
+      const uint32_t v = ATR ? atc.voff(d, k0, K, lda) : atr.voff(d, k0, K, lda);
+      dma16(ra, live ? v : OOB, a_wave + stage * STAGE + d * 1024);
+    } else {
+      const uint32_t v = BTR ? btc.voff(d - NIA, k0, K, ldb) : btr.voff(d - NIA, k0, K, ldb);
+      dma16(rb, live ? v : OOB, b_wave + stage * STAGE + (d - NIA) * 1024);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+#pragma unroll
+  for (int s = 0; s < NS - 1; s++) {
+#pragma unroll
+    for (int d = 0; d < LPT; d++) fire(d, s, s, s < nk);
+  }
+
+  // LDS reads per 16-wide k-substep and the MFMA : read interleave the scheduler is asked for
+  constexpr int NR = (ATR ? 2 : 1) * TM + (BTR ? 2 : 1) * TN, NMFMA = TM * TN;
+  constexpr int DPK = (LPT + KS - 1) / KS;  // DMA instructions fired per k-substep
+  int stage = 0;
+  for (int kt = 0; kt < nk; kt++) {
+    // tile kt has landed once at most the loads of the NS-2 younger tiles are still in flight
+    wait_vmcnt<(NS - 2) * LPT>();
+    __syncthreads();
+    const bool prefetch = kt + NS - 1 < nk;
+    const int pstage = stage == 0 ? NS - 1 : stage - 1;
+    const unsigned char* sa = smem + stage * STAGE;
+    const unsigned char* sb = sa + A_BYTES;
+    bf16x8 af[2][TM], bfr[2][TN];
+    auto lfrag = [&](int kk, int buf) {
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+        af[buf][i] = ATR ? AT_C::frag(sa, wm + i * 32, kk, lane) : AT_R::frag(sa, wm + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+        bfr[buf][j] = BTR ? BT_C::frag(sb, wn + j * 32, kk, lane) : BT_R::frag(sb, wn + j * 32, kk, lane);
+    };
+    lfrag(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KS; kk++) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk + 1 < KS) lfrag(kk + 1, (kk + 1) & 1);
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        if (i == TM / 2) {  // the next tile's DMA goes out between the two halves of the MFMA block
+#pragma unroll
+          for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, kt + NS - 1, pstage, prefetch);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; j++)  // operands swapped: the lane ends up with 4 consecutive columns of one row
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      }
+      if (kk + 1 < KS && NMFMA >= 16) {  // spread the next substep's LDS reads over the first half of the MFMAs
+#pragma unroll
+        for (int g = 0; g < NMFMA / 2; g++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // 1 MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, NR / (NMFMA / 2), 0);  // its share of the DS reads
+        }
+      }
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+  wait_vmcnt<0>();  // nothing of this wave may still be writing LDS when it leaves
+
+  // Epilogue.  Element (g*4 + r) of lane l is C[row l%32][col (l/32)*4 + 8g + r] of its 32x32 tile.
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int row = m0 + wm + i * 32 + (lane & 31);
+    if (row >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        const int col = n0 + wn + j * 32 + (lane >> 5) * 4 + 8 * g;
+        if (col >= N) continue;
+        const int64_t off = int64_t(row) * ldc + col;
+        float v[4] = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+        if (EPI == EPI_BF16) {
+          if (R) {
+            const uint2 rr = *reinterpret_cast<const uint2*>(R + off);
+            v[0] += __uint_as_float(rr.x << 16);
+            v[1] += __uint_as_float(rr.x & 0xffff0000u);
+            v[2] += __uint_as_float(rr.y << 16);
+            v[3] += __uint_as_float(rr.y & 0xffff0000u);
+          }
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + off) = o;
+        } else {
+          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + off);
+          float4 t = *c;
+          t.x += v[0]; t.y += v[1]; t.z += v[2]; t.w += v[3];
+          *c = t;
+        }
+      }
+  }
+}
+
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI>
+hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
+                  int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
+  constexpr int LDS = NS * (BM + BN) * BK * 2;
+  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, tm);
+  return hipGetLastError();
+}
+
+template <bool ATR, bool BTR, int EPI>
+hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
+                    int64_t ldb, int64_t ldc, uint32_t ab, uint32_t bb, hipStream_t st) {
+  const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
+  if (big_tiles >= 192) return launch<256, 256, 64, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ab, bb, st);
+  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ab, bb, st);
+}
+
+}  // namespace
+
+namespace mls {
+
+// true if the DMA path can run this problem: every operand (plus one tile of slack) addressable with a
+// 31-bit byte offset
+bool gemm_bf16_dma_ok(int mode, int M, int N, int K, int64_t lda, int64_t ldb) {
+  const int64_t a_rows = mode == GEMM_TN ? K : M, b_rows = mode == GEMM_NT ? N : K;
+  const int64_t lim = int64_t(1) << 31;
+  return (a_rows + 512) * lda * 2 < lim && (b_rows + 512) * ldb * 2 < lim && K > 0;
+}
+
+hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
+                         int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st) {
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* b = static_cast<const bf16_t*>(B);
+  const bf16_t* r = static_cast<const bf16_t*>(R);
+  if (M == 0 || N == 0) return hipSuccess;
+  const int64_t a_rows = mode == GEMM_TN ? K : M, b_rows = mode == GEMM_NT ? N : K;
+  const uint32_t ab = uint32_t(a_rows * lda * 2), bb = uint32_t(b_rows * ldb * 2);
+  switch (mode) {
+    case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
+    case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
+    case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mls

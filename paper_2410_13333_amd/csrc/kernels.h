@@ -12,6 +12,11 @@ enum { DT_BF16 = 0, DT_FP32 = 1 };
 // ---- contractions (gemm_bf16.hip, gemm_f32.hip); modes as documented at mls_gemm; leading dims in elements
 hipError_t gemm_bf16(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                      int64_t ldb, int64_t ldc, hipStream_t st);
+// the two implementations behind gemm_bf16: LDS-DMA main path and the register-staged fallback for operands
+// too large for 31-bit buffer offsets
+bool gemm_bf16_dma_ok(int mode, int M, int N, int K, int64_t lda, int64_t ldb);
+hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
+                         int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st);
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, hipStream_t st);
 
