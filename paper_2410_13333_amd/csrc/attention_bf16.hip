@@ -19,6 +19,26 @@
 
 namespace {
 
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// 16 bytes per lane from a raw buffer straight into LDS (64 lanes fill 1 KiB at lds_byte); out-of-range lanes
+// are zero-filled.  Inline asm so that the waits are placed by hand (see gemm_bf16_dma.hip).
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_byte), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  i32x4 r;
+  r[0] = (int)(uint32_t)a;
+  r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+constexpr uint32_t OOB = 0x80000000u;
+
 constexpr int AT_THREADS = 256;
 constexpr int TR = 64;  // rows of an LDS tile
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
@@ -38,26 +58,36 @@ __device__ __forceinline__ int toff(int row, int col) {
 
 template <int D>
 struct Tile {
-  static constexpr int CHUNKS = TR * D / 8 / AT_THREADS;  // 16-byte chunks per thread
-  // rows [row0, row0+64) x cols [col0, col0+D) of a row-major matrix; rows >= nrows read as zero
-  static __device__ __forceinline__ void gload(const bf16_t* __restrict__ g, int64_t ld, int row0, int col0, int nrows,
-                                               uint4 (&r)[CHUNKS]) {
+  static constexpr int BYTES = TR * D * 2;
+  static constexpr int NI = BYTES / 1024 / 4;  // DMA instructions per wave per tile
+  // Per-lane source offsets (bytes, relative to element (row0, col0) of the source matrix) of this wave's DMA
+  // instructions: instruction q = wave*NI + i fills LDS bytes [1024 q, 1024 q + 1024) of the tile, and the lane
+  // that writes a given 16-byte slot fetches the chunk the swizzle assigns to it.
+  uint32_t off[NI];
+  __device__ __forceinline__ void init(int64_t ld, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < CHUNKS; i++) {
-      const int id = threadIdx.x + i * AT_THREADS;
-      const int rr = id / (D / 8), cc = (id % (D / 8)) * 8;
-      if (row0 + rr < nrows)
-        r[i] = *reinterpret_cast<const uint4*>(g + int64_t(row0 + rr) * ld + col0 + cc);
-      else
-        r[i] = make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < NI; i++) {
+      const int q = wave * NI + i;
+      int row, chunk;
+      if (D == 128) {
+        row = q * 4 + (lane >> 4);
+        chunk = (lane & 15) ^ (((row & 3) << 2) | ((row >> 2) & 3));
+      } else {
+        const int line = q * 4 + (lane >> 4);
+        const int idx = (lane & 15) ^ (((line & 1) << 2) | ((line >> 1) & 3));
+        row = line * 2 + (idx >> 3);
+        chunk = idx & 7;
+      }
+      off[i] = uint32_t((int64_t(row) * ld + chunk * 8) * 2);
     }
   }
-  static __device__ __forceinline__ void lstore(bf16_t* t, const uint4 (&r)[CHUNKS]) {
+  // rows [row0, row0+64) x cols [col0, col0+D) of the matrix behind rsrc (row stride ld) -> tile at LDS byte
+  // address `tile`; rows at or beyond the end of the buffer are zero-filled; live = false sends nothing useful
+  __device__ __forceinline__ void dma(i32x4 rsrc, int64_t ld, int row0, int col0, uint32_t tile, int wave,
+                                      bool live) const {
+    const uint32_t base = uint32_t((int64_t(row0) * ld + col0) * 2);
 #pragma unroll
-    for (int i = 0; i < CHUNKS; i++) {
-      const int id = threadIdx.x + i * AT_THREADS;
-      *reinterpret_cast<uint4*>(t + toff<D>(id / (D / 8), (id % (D / 8)) * 8)) = r[i];
-    }
+    for (int i = 0; i < NI; i++) dma16(rsrc, live ? base + off[i] : OOB, tile + (wave * NI + i) * 1024);
   }
   // A operand, rows = tile rows rt*32 .. +31, k = tile columns kk*16 .. +15
   static __device__ __forceinline__ bf16x8 frag_rows(const bf16_t* t, int rt, int kk, int lane) {
@@ -114,20 +144,30 @@ __device__ __forceinline__ void store_t(bf16_t* __restrict__ out, int64_t ld, in
 }
 
 // ================================================================ forward
-// grid (q blocks of 128, n_q, b); wave w owns query rows q0 + 32w .. +31; loops over KV blocks of 64.
+// grid (n_q, q blocks of 128, b) with the longest query blocks dispatched first over all heads; wave w owns
+// query rows q0 + 32w .. +31; loops over KV blocks of 64.  Two workgroups fit a CU.
 template <int D>
-__global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                               float* __restrict__ lse, int S, int nq, int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];  // [buffer][K|V]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qb = gridDim.x - 1 - blockIdx.x;  // longest rows first
-  const int hq = blockIdx.y, bi = blockIdx.z, hk = hq / (nq / nkv);
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][K|V]
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qb = gridDim.y - 1 - blockIdx.y;  // longest rows first
+  const int hq = blockIdx.x, bi = blockIdx.z, hk = hq / (nq / nkv);
   const int64_t ld = int64_t(nq + 2 * nkv) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
   const float sc = rsqrtf((float)D) * LOG2E;
+  const i32x4 rsrc = make_rsrc(base, uint32_t(int64_t(S) * ld * 2));
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS bf16_t*)&lds[0][0][0];
+  TL tl;
+  tl.init(ld, wave, lane);
+  auto issue = [&](int blk, bool live) {  // K and V rows [64 blk, 64 blk + 64) into buffer blk & 1
+    const uint32_t t = lds0 + (blk & 1) * 2 * TL::BYTES;
+    tl.dma(rsrc, ld, blk * TR, (nq + hk) * D, t, wave, live);
+    tl.dma(rsrc, ld, blk * TR, (nq + nkv + hk) * D, t + TL::BYTES, wave, live);
+  };
 
   bf16x8 qf[KD];
 #pragma unroll
@@ -140,19 +180,12 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
 
   const int kv_end = min(S, q0 + 128);
   const int nblk = (kv_end + TR - 1) / TR;
-  uint4 rk[TL::CHUNKS], rv[TL::CHUNKS];
-  TL::gload(base, ld, 0, (nq + hk) * D, S, rk);
-  TL::gload(base, ld, 0, (nq + nkv + hk) * D, S, rv);
-  TL::lstore(lds[0][0], rk);
-  TL::lstore(lds[0][1], rv);
-  __syncthreads();
+  issue(0, true);
   for (int blk = 0; blk < nblk; blk++) {
     const int cur = blk & 1, j0 = blk * TR;
-    const bool more = blk + 1 < nblk;
-    if (more) {
-      TL::gload(base, ld, j0 + TR, (nq + hk) * D, S, rk);
-      TL::gload(base, ld, j0 + TR, (nq + nkv + hk) * D, S, rv);
-    }
+    wait_dma();       // this wave's part of block blk has landed ...
+    __syncthreads();  // ... and so has everyone's; all reads of the other buffer are retired
+    issue(blk + 1, blk + 1 < nblk);
     if (j0 <= qw + 31) {  // wave-uniform: some (i, j) pair of this wave is unmasked
       const bf16_t* ks = lds[cur][0];
       const bf16_t* vs = lds[cur][1];
@@ -204,12 +237,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(vs, t, jt * 2 + s, lane), pf, acc[t], 0, 0, 0);
         }
     }
-    if (more) {
-      TL::lstore(lds[cur ^ 1][0], rk);
-      TL::lstore(lds[cur ^ 1][1], rv);
-    }
-    __syncthreads();
   }
+  wait_dma();
   l += __shfl_xor(l, 32, 64);
   const float inv = 1.f / l;
   bf16_t* ob = o + int64_t(bi) * S * (int64_t(nq) * D);
@@ -222,22 +251,31 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
 // Same decomposition as the forward.  Per KV block: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - delta),
 // dQ^T += K^T dS^T.
 template <int D>
-__global__ __launch_bounds__(AT_THREADS) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
                                                              const bf16_t* __restrict__ d_o,
                                                              const float* __restrict__ lse,
                                                              const float* __restrict__ delta,
                                                              bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int hq = blockIdx.y, bi = blockIdx.z, hk = hq / (nq / nkv);
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qb = gridDim.y - 1 - blockIdx.y;
+  const int hq = blockIdx.x, bi = blockIdx.z, hk = hq / (nq / nkv);
   const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
   const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
   const float scale = rsqrtf((float)D), sc = scale * LOG2E;
+  const i32x4 rsrc = make_rsrc(base, uint32_t(int64_t(S) * ld * 2));
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS bf16_t*)&lds[0][0][0];
+  TL tl;
+  tl.init(ld, wave, lane);
+  auto issue = [&](int blk, bool live) {
+    const uint32_t t = lds0 + (blk & 1) * 2 * TL::BYTES;
+    tl.dma(rsrc, ld, blk * TR, (nq + hk) * D, t, wave, live);
+    tl.dma(rsrc, ld, blk * TR, (nq + nkv + hk) * D, t + TL::BYTES, wave, live);
+  };
 
   bf16x8 qf[KD], dof[KD];
 #pragma unroll
@@ -255,19 +293,12 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dq_kernel(const bf16_t* __res
 
   const int kv_end = min(S, q0 + 128);
   const int nblk = (kv_end + TR - 1) / TR;
-  uint4 rk[TL::CHUNKS], rv[TL::CHUNKS];
-  TL::gload(base, ld, 0, (nq + hk) * D, S, rk);
-  TL::gload(base, ld, 0, (nq + nkv + hk) * D, S, rv);
-  TL::lstore(lds[0][0], rk);
-  TL::lstore(lds[0][1], rv);
-  __syncthreads();
+  issue(0, true);
   for (int blk = 0; blk < nblk; blk++) {
     const int cur = blk & 1, j0 = blk * TR;
-    const bool more = blk + 1 < nblk;
-    if (more) {
-      TL::gload(base, ld, j0 + TR, (nq + hk) * D, S, rk);
-      TL::gload(base, ld, j0 + TR, (nq + nkv + hk) * D, S, rv);
-    }
+    wait_dma();
+    __syncthreads();
+    issue(blk + 1, blk + 1 < nblk);
     if (j0 <= qw + 31) {
       const bf16_t* ks = lds[cur][0];
       const bf16_t* vs = lds[cur][1];
@@ -302,19 +333,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dq_kernel(const bf16_t* __res
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ks, t, jt * 2 + s, lane), df, acc[t], 0, 0, 0);
         }
     }
-    if (more) {
-      TL::lstore(lds[cur ^ 1][0], rk);
-      TL::lstore(lds[cur ^ 1][1], rv);
-    }
-    __syncthreads();
   }
+  wait_dma();
   bf16_t* out = dqkv + int64_t(bi) * S * ld;
 #pragma unroll
   for (int t = 0; t < DT; t++) store_t(out, ld, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
 }
 
 // ================================================================ backward: dK, dV
-// grid (kv blocks of 128, n_kv, b); wave w owns key rows j0 + 32w .. +31 and keeps their K and V as B operands.
+// grid (n_kv, kv blocks of 128, b), longest first; wave w owns key rows j0 + 32w .. +31 and keeps their K and V as B operands.
 // Loops over the query heads of the group and the query blocks of 64 rows at or below the diagonal:
 // S = Q K^T and dP = dO V^T (lane column = key row), dV^T += dO^T P, dK^T += Q^T dS.
 template <int D>
@@ -325,10 +352,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
                                                               bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
-  __shared__ float stat[2][2][TR];                                     // [buffer][lse*log2e | delta]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int kb = blockIdx.x, hk = blockIdx.y, bi = blockIdx.z, grp = nq / nkv;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
+  __shared__ float stat[2][2][TR];                                       // [buffer][lse*log2e | delta]
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kb = blockIdx.y, hk = blockIdx.x, bi = blockIdx.z, grp = nq / nkv;
   const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
@@ -347,33 +374,37 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
 
   const int qb0 = j0 / TR, nqb = (S + TR - 1) / TR - qb0;  // query blocks per head
   const int niter = nqb > 0 ? nqb * grp : 0;
-  uint4 rq[TL::CHUNKS], rd[TL::CHUNKS];
-  float rs = 0.f;  // threads 0..63: lse*log2e of row tid; threads 64..127: delta of row tid-64
-  auto gl = [&](int it) {
-    const int hq = hk * grp + it / nqb, i0 = (qb0 + it % nqb) * TR;
-    TL::gload(base, ld, i0, hq * D, S, rq);
-    TL::gload(dob, ldo, i0, hq * D, S, rd);
-    if (threadIdx.x < 2 * TR) {
+  const i32x4 rq_src = make_rsrc(base, uint32_t(int64_t(S) * ld * 2)), rd_src = make_rsrc(dob, uint32_t(int64_t(S) * ldo * 2));
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS bf16_t*)&lds[0][0][0];
+  TL tq, td;
+  tq.init(ld, wave, lane);
+  td.init(ldo, wave, lane);
+  // iteration `it`: Q and dO rows of one 64-row query block of one head of the group -> buffer it & 1; the row
+  // statistics go through registers (threads 0..63: lse*log2e of row tid; threads 64..127: delta of row tid-64)
+  float rs = 0.f;
+  auto issue = [&](int it, bool live) {
+    const int hq = hk * grp + (live ? it / nqb : 0), i0 = (qb0 + (live ? it % nqb : 0)) * TR;
+    const uint32_t t = lds0 + (it & 1) * 2 * TL::BYTES;
+    tq.dma(rq_src, ld, i0, hq * D, t, wave, live);
+    td.dma(rd_src, ldo, i0, hq * D, t + TL::BYTES, wave, live);
+    if (live && threadIdx.x < 2 * TR) {
       const int r = threadIdx.x & (TR - 1);
       const int64_t si = (int64_t(bi) * nq + hq) * S + i0 + r;
       rs = 0.f;
       if (i0 + r < S) rs = threadIdx.x < TR ? lse[si] * LOG2E : delta[si];
     }
   };
-  auto ls = [&](int buf) {
-    TL::lstore(lds[buf][0], rq);
-    TL::lstore(lds[buf][1], rd);
-    if (threadIdx.x < 2 * TR) stat[buf][threadIdx.x >> 6][threadIdx.x & (TR - 1)] = rs;
+  // the statistics fetched by issue(it) are stored after the compute of iteration it-1 (or before the loop)
+  auto put_stat = [&](int it) {
+    if (threadIdx.x < 2 * TR) stat[it & 1][threadIdx.x >> 6][threadIdx.x & (TR - 1)] = rs;
   };
-  if (niter > 0) {
-    gl(0);
-    ls(0);
-  }
-  __syncthreads();
+  issue(0, niter > 0);
+  put_stat(0);
   for (int it = 0; it < niter; it++) {
     const int cur = it & 1, i0 = (qb0 + it % nqb) * TR;
-    const bool more = it + 1 < niter;
-    if (more) gl(it + 1);
+    wait_dma();
+    __syncthreads();
+    issue(it + 1, it + 1 < niter);
     if (i0 + TR - 1 >= jw) {  // wave-uniform: some query row at or below this wave's first key row
       const bf16_t* qs = lds[cur][0];
       const bf16_t* ds_ = lds[cur][1];
@@ -411,9 +442,9 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
           }
         }
     }
-    if (more) ls(cur ^ 1);
-    __syncthreads();
+    if (it + 1 < niter) put_stat(it + 1);
   }
+  wait_dma();
   bf16_t* out = dqkv + int64_t(bi) * S * ld;
 #pragma unroll
   for (int t = 0; t < DT; t++) {
@@ -428,7 +459,7 @@ namespace mls {
 
 hipError_t attn_fwd_bf16(const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
   if (b == 0 || S == 0) return hipSuccess;
-  dim3 grid((S + 127) / 128, nq, b);
+  dim3 grid(nq, (S + 127) / 128, b);
   if (d == 128)
     hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (bf16_t*)o, lse, S, nq, nkv);
   else if (d == 64)
@@ -443,7 +474,7 @@ hipError_t attn_bwd_bf16(const void* qkv, const void* o, const float* lse, const
   if (b == 0 || S == 0) return hipSuccess;
   hipError_t e = attn_delta(DT_BF16, o, d_o, delta, b, S, nq, d, st);
   if (e != hipSuccess) return e;
-  dim3 gq((S + 127) / 128, nq, b), gk((S + 127) / 128, nkv, b);
+  dim3 gq(nq, (S + 127) / 128, b), gk(nkv, (S + 127) / 128, b);
   if (d == 128) {
     hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
                        delta, (bf16_t*)dqkv, S, nq, nkv);

@@ -7,10 +7,11 @@
 namespace {
 
 constexpr int EW_THREADS = 256;
-constexpr int NORM_MAXC = 8;  // 16-byte chunks per thread a row may span: hidden <= 8*8*256 = 16384
+// NORM_MAXC = 16-byte chunks per thread a row may span (template argument MAXC of the norm kernels):
+// hidden <= MAXC * 8 * 256; instantiated for 2, 4 and 8 so that narrow rows do not pay for wide ones in registers
 
 // ---------------------------------------------------------------- RMSNorm forward: one workgroup per row
-template <typename T>
+template <typename T, int NORM_MAXC>
 __global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                                  T* __restrict__ a, float* __restrict__ rstd, int h,
                                                                  float eps) {
@@ -47,7 +48,7 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __rest
 // ---------------------------------------------------------------- RMSNorm backward
 // Workgroup w handles rows w, w + gridDim.x, ...; it keeps its share of the column sums for dgamma in
 // registers and writes them to partial[w][:], which a second kernel adds up in a fixed order.
-template <typename T>
+template <typename T, int NORM_MAXC>
 __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ da, const T* __restrict__ x,
                                                                  const T* __restrict__ gamma,
                                                                  const float* __restrict__ rstd,
@@ -103,12 +104,17 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
   }
 }
 
-__global__ void colsum_add_kernel(const float* __restrict__ partial, float* __restrict__ out, int nblocks, int h) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= h) return;
+// out[c] += sum_b partial[b][c]: 64 columns per workgroup, 4 row groups per column, fixed summation order
+__global__ __launch_bounds__(256) void colsum_add_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                                         int nblocks, int h) {
+  __shared__ float red[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
   float s = 0.f;
-  for (int b = 0; b < nblocks; b++) s += partial[int64_t(b) * h + c];
-  out[c] += s;
+  if (c < h)
+    for (int b = grp; b < nblocks; b += 4) s += partial[int64_t(b) * h + c];
+  red[grp][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (grp == 0 && c < h) out[c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
 // ---------------------------------------------------------------- rotary embedding, in place
@@ -225,30 +231,38 @@ namespace mls {
 hipError_t rmsnorm_fwd(int dt, const void* x, const void* gamma, void* a, float* r, int T, int h, float eps,
                        hipStream_t st) {
   if (T == 0) return hipSuccess;
-  if (dt == DT_BF16)
-    hipLaunchKernelGGL(rmsnorm_fwd_kernel<bf16_t>, dim3(T), dim3(EW_THREADS), 0, st, (const bf16_t*)x,
-                       (const bf16_t*)gamma, (bf16_t*)a, r, h, eps);
-  else
-    hipLaunchKernelGGL(rmsnorm_fwd_kernel<float>, dim3(T), dim3(EW_THREADS), 0, st, (const float*)x,
-                       (const float*)gamma, (float*)a, r, h, eps);
+#define FWD(TY, C)                                                                                             \
+  hipLaunchKernelGGL((rmsnorm_fwd_kernel<TY, C>), dim3(T), dim3(EW_THREADS), 0, st, (const TY*)x, (const TY*)gamma, \
+                     (TY*)a, r, h, eps)
+  const int mc = h <= 4096 ? 2 : h <= 8192 ? 4 : 8;
+  if (dt == DT_BF16) {
+    if (mc == 2) FWD(bf16_t, 2); else if (mc == 4) FWD(bf16_t, 4); else FWD(bf16_t, 8);
+  } else {
+    if (mc == 2) FWD(float, 2); else if (mc == 4) FWD(float, 4); else FWD(float, 8);
+  }
+#undef FWD
   return hipGetLastError();
 }
 
-int rmsnorm_bwd_blocks(int T) { return T < 1024 ? (T > 0 ? T : 1) : 1024; }
+int rmsnorm_bwd_blocks(int T) { return T < 512 ? (T > 0 ? T : 1) : 512; }
 
 hipError_t rmsnorm_bwd(int dt, const void* da, const void* x, const void* gamma, const float* r, const void* dres,
                        void* dx, float* dgamma, float* partial, int T, int h, hipStream_t st) {
   if (T == 0) return hipSuccess;
   const int nb = rmsnorm_bwd_blocks(T);
-  if (dt == DT_BF16)
-    hipLaunchKernelGGL(rmsnorm_bwd_kernel<bf16_t>, dim3(nb), dim3(EW_THREADS), 0, st, (const bf16_t*)da,
-                       (const bf16_t*)x, (const bf16_t*)gamma, r, (const bf16_t*)dres, (bf16_t*)dx, partial, T, h);
-  else
-    hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nb), dim3(EW_THREADS), 0, st, (const float*)da, (const float*)x,
-                       (const float*)gamma, r, (const float*)dres, (float*)dx, partial, T, h);
+#define BWD(TY, C)                                                                                               \
+  hipLaunchKernelGGL((rmsnorm_bwd_kernel<TY, C>), dim3(nb), dim3(EW_THREADS), 0, st, (const TY*)da, (const TY*)x,     \
+                     (const TY*)gamma, r, (const TY*)dres, (TY*)dx, partial, T, h)
+  const int mc = h <= 4096 ? 2 : h <= 8192 ? 4 : 8;
+  if (dt == DT_BF16) {
+    if (mc == 2) BWD(bf16_t, 2); else if (mc == 4) BWD(bf16_t, 4); else BWD(bf16_t, 8);
+  } else {
+    if (mc == 2) BWD(float, 2); else if (mc == 4) BWD(float, 4); else BWD(float, 8);
+  }
+#undef BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 255) / 256), dim3(256), 0, st, partial, dgamma, nb, h);
+  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 63) / 64), dim3(256), 0, st, partial, dgamma, nb, h);
   return hipGetLastError();
 }
 

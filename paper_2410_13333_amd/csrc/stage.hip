@@ -133,6 +133,8 @@ int check_config(const mls_config& c) {
   const int64_t widest = std::max<int64_t>(2 * int64_t(c.ffn), int64_t(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
   if (T > (1 << 24) || widest > (1 << 24) || T * widest > (int64_t(1) << 40))
     return fail(MLS_E_CONFIG, "tokens per micro-batch or layer width too large");
+  if (c.dtype == MLS_BF16 && int64_t(c.seq + 128) * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 2 >= (int64_t(1) << 31))
+    return fail(MLS_E_CONFIG, "seq * (q_dim + 2 kv_dim) must stay below 2^30 elements for bf16 storage");
   return MLS_OK;
 }
 

@@ -174,3 +174,12 @@ def test_weight_gradient_contraction_given_identical_operands_1e4():
         e = rel_err(gh[off:off + rows * cols].reshape(rows, cols), r)
         assert e <= 1e-4, (name, e)
     st.close()
+
+
+def test_wide_hidden_rows_span_many_chunks():
+    """hidden above 4096 and above 8192 exercises the wider register tilings of the RMSNorm kernels."""
+    for hidden in (4104, 8200):
+        sh = synth.StageShape(hidden=hidden, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64, seq=72, micro_batch=1,
+                              layers=1, microbatches=2)
+        _check(sh, [1, 1], 1e-2)
+        _check(sh.with_(dtype="fp32"), [1], 1e-4)
