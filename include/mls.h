@@ -160,10 +160,12 @@ int mls_stage_timing_read(mls_stage* s, double* ms /*host*/, int64_t* launches /
  * mode 0: C[M,N] = A[M,K] * B[K,N] (+ R[M,N] if R != NULL)   forward projections (+ residual)
  * mode 1: C[M,N] = A[M,K] * B[N,K]^T                          data gradients
  * mode 2: C[M,N] += A[K,M]^T * B[K,N], C fp32                 weight gradients, accumulated
- * A, B, R and (modes 0/1) C are in storage type `dtype`; all dims multiples of 8.
+ * A, B, R and (modes 0/1) C are in storage type `dtype`; all dims multiples of 8.  lda, ldb, ldc are the row
+ * strides in elements of A, B and C (R shares ldc); 0 means dense (the row length of that operand); otherwise
+ * a multiple of 8 not below the row length.
  * Runs on `hip_stream`.  Errors: MLS_E_NULL, MLS_E_CONFIG, MLS_E_HIP. */
-int mls_gemm(int32_t dtype, int32_t mode, const void* A, const void* B, void* C, const void* R, int64_t M,
-             int64_t N, int64_t K, void* hip_stream);
+int mls_gemm(int32_t dtype, int32_t mode, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+             const void* R, int64_t M, int64_t N, int64_t K, void* hip_stream);
 
 /* Message for the last error returned on this thread (host string, never NULL). */
 const char* mls_last_error(void);

@@ -14,6 +14,12 @@ mathematics, so the oracle is the plain definition: the full S x S score matrix 
 is blocked, fused or reordered.  All arithmetic is fp64; callers pass values already rounded to the
 storage type when they model a bf16 run.
 
+Storage-rounded mode.  layer_forward / layer_backward take an optional `store(name, tensor)` hook that is
+applied to every tensor the stage writes to memory in its storage type (the names are listed at _STORE_POINTS).
+With the default (identity) the oracle is the exact fp64 function that the pins below fix.  With a hook that
+rounds to bf16 it states what a path that keeps every intermediate tensor in bf16, and is otherwise exact,
+computes; the arithmetic between two stores is the same fp64 code either way.
+
 Parity pins (tests/test_oracle_*.py): central finite differences on every parameter and on dX, softmax
 rows summing to one, causality, RoPE norm preservation / relative-position property, the RMSNorm closed
 form, attention special cases, a brute-force scalar-loop re-derivation on tiny shapes, linearity of
@@ -121,82 +127,98 @@ def swiglu_bwd(dz, g, u):
 
 # ---------------------------------------------------------------- one decoder layer
 
+# tensors written to memory by one layer, in order: forward, then backward ("_pre" = before the rotary step,
+# which rewrites the q and k parts in place and leaves v as it is)
+_STORE_POINTS = ("a", "qkv_pre", "qkv", "o", "h", "b", "gu", "z", "y",
+                 "dz", "dgu", "db", "dh", "dc", "dqkv_pre", "dqkv", "da", "dx")
 
-def layer_forward(x, w, sh):
+
+def _identity(name, t):
+    return t
+
+
+
+def layer_forward(x, w, sh, store=None):
     """x: [b,S,h]; w: dict gamma1,w_qkv,w_o,gamma2,w_gu,w_d (row-major [in,out]); sh: shape object with
     hidden,n_q_heads,n_kv_heads,head_dim,ffn,rms_eps,rope_base.  Returns (y, cache)."""
+    st = store or _identity
     b, S, h = x.shape
     nq, nkv, d, f = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn
     qd, kvd = nq * d, nkv * d
     X = x.reshape(b * S, h)
     A, r1 = rmsnorm_fwd(X, w["gamma1"], sh.rms_eps)
-    QKV = A @ w["w_qkv"]
+    A = st("a", A)
+    QKV = st("qkv_pre", A @ w["w_qkv"])
     ang = rope_angles(S, d, sh.rope_base)
-    q = rope_apply(QKV[:, :qd].reshape(b, S, nq, d), ang)
-    k = rope_apply(QKV[:, qd:qd + kvd].reshape(b, S, nkv, d), ang)
+    qk = st("qkv", rope_apply(QKV[:, :qd + kvd].reshape(b, S, nq + nkv, d), ang))
+    q, k = qk[:, :, :nq, :], qk[:, :, nq:, :]
     v = QKV[:, qd + kvd:].reshape(b, S, nkv, d)
     o, p = attention_fwd(q, k, v)
+    o = st("o", o)
     C = o.reshape(b * S, qd)
-    H = X + C @ w["w_o"]
+    H = st("h", X + C @ w["w_o"])
     B, r2 = rmsnorm_fwd(H, w["gamma2"], sh.rms_eps)
-    GU = B @ w["w_gu"]
+    B = st("b", B)
+    GU = st("gu", B @ w["w_gu"])
     G, U = GU[:, :f], GU[:, f:]
-    Z = swiglu_fwd(G, U)
-    Y = H + Z @ w["w_d"]
+    Z = st("z", swiglu_fwd(G, U))
+    Y = st("y", H + Z @ w["w_d"])
     cache = dict(X=X, A=A, r1=r1, q=q, k=k, v=v, p=p, C=C, H=H, B=B, r2=r2, G=G, U=U, Z=Z, ang=ang)
     return Y.reshape(b, S, h), cache
 
 
-def layer_backward(dy, w, cache, sh):
+def layer_backward(dy, w, cache, sh, store=None):
     """Reverse mode of layer_forward.  Returns (dx, grads dict with the same keys as w)."""
+    st = store or _identity
     b, S, h = dy.shape
     nq, nkv, d, f = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn
     qd, kvd = nq * d, nkv * d
     c = cache
     dY = dy.reshape(b * S, h)
     g = {}
-    dZ = dY @ w["w_d"].T
+    dZ = st("dz", dY @ w["w_d"].T)
     g["w_d"] = c["Z"].T @ dY
     dG, dU = swiglu_bwd(dZ, c["G"], c["U"])
-    dGU = np.concatenate([dG, dU], axis=1)
-    dB = dGU @ w["w_gu"].T
+    dGU = st("dgu", np.concatenate([dG, dU], axis=1))
+    dB = st("db", dGU @ w["w_gu"].T)
     g["w_gu"] = c["B"].T @ dGU
     dHn, g["gamma2"] = rmsnorm_bwd(dB, c["H"], w["gamma2"], c["r2"])
-    dH = dY + dHn
-    dC = dH @ w["w_o"].T
+    dH = st("dh", dY + dHn)
+    dC = st("dc", dH @ w["w_o"].T)
     g["w_o"] = c["C"].T @ dH
     dq, dk, dv = attention_bwd(dC.reshape(b, S, nq, d), c["q"], c["k"], c["v"], c["p"])
-    dq = rope_apply(dq, c["ang"], sign=-1.0)
-    dk = rope_apply(dk, c["ang"], sign=-1.0)
+    dq, dk, dv = st("dqkv_pre", dq), st("dqkv_pre", dk), st("dqkv_pre", dv)
+    dq = st("dqkv", rope_apply(dq, c["ang"], sign=-1.0))
+    dk = st("dqkv", rope_apply(dk, c["ang"], sign=-1.0))
     dQKV = np.concatenate([dq.reshape(b * S, qd), dk.reshape(b * S, kvd), dv.reshape(b * S, kvd)], axis=1)
-    dA = dQKV @ w["w_qkv"].T
+    dA = st("da", dQKV @ w["w_qkv"].T)
     g["w_qkv"] = c["A"].T @ dQKV
     dXn, g["gamma1"] = rmsnorm_bwd(dA, c["X"], w["gamma1"], c["r1"])
-    dX = dH + dXn
+    dX = st("dx", dH + dXn)
     return dX.reshape(b, S, h), g
 
 # ---------------------------------------------------------------- the stage
 
 
-def stage_forward(x, weights, sh, k_layers=None):
+def stage_forward(x, weights, sh, k_layers=None, store=None):
     """Layers 0..k-1 composed.  weights: list of per-layer dicts.  k = 0 is the identity.
     Returns (y, list of per-layer caches)."""
     k = len(weights) if k_layers is None else k_layers
     caches = []
     y = np.array(x, dtype=np.float64)
     for l in range(k):
-        y, c = layer_forward(y, weights[l], sh)
+        y, c = layer_forward(y, weights[l], sh, store)
         caches.append(c)
     return y, caches
 
 
-def stage_backward(dy, weights, caches, sh):
+def stage_backward(dy, weights, caches, sh, store=None):
     """Reverse of stage_forward for one micro-batch: returns (dx, list of per-layer grad dicts)."""
     k = len(caches)
     grads = [None] * k
     d = np.array(dy, dtype=np.float64)
     for l in range(k - 1, -1, -1):
-        d, grads[l] = layer_backward(d, weights[l], caches[l], sh)
+        d, grads[l] = layer_backward(d, weights[l], caches[l], sh, store)
     return d, grads
 
 

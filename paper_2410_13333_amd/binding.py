@@ -56,7 +56,7 @@ def lib():
         L.mls_stage_debug_read.argtypes = [vp, i32, i32, i32, vp]
         L.mls_stage_timing.argtypes = [vp, i32]
         L.mls_stage_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
-        L.mls_gemm.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.mls_gemm.argtypes = [i32, i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, vp]
         L.mls_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -169,7 +169,8 @@ class Stage:
 
 
 def gemm(mode, a, b, c, r=None, stream=None):
-    """Stand-alone call of the stage's contraction kernel; shapes as documented at mls_gemm."""
+    """Stand-alone call of the stage's contraction kernel; shapes as documented at mls_gemm.  Operands may be
+    column slices of wider row-major buffers (row stride = stride(0))."""
     import torch
     dtype = MLS_BF16 if a.dtype == torch.bfloat16 else MLS_FP32
     if mode == 0:
@@ -178,5 +179,9 @@ def gemm(mode, a, b, c, r=None, stream=None):
         (M, K), N = a.shape, b.shape[0]
     else:
         (K, M), N = a.shape, b.shape[1]
+    for t in (a, b, c) + ((r,) if r is not None else ()):
+        assert t.stride(1) == 1
+    assert r is None or r.stride(0) == c.stride(0)
     st = stream if stream is not None else torch.cuda.current_stream()
-    _check(lib().mls_gemm(dtype, mode, _ptr(a), _ptr(b), _ptr(c), _ptr(r), M, N, K, C.c_void_p(st.cuda_stream)))
+    _check(lib().mls_gemm(dtype, mode, _ptr(a), a.stride(0), _ptr(b), b.stride(0), _ptr(c), c.stride(0), _ptr(r),
+                          M, N, K, C.c_void_p(st.cuda_stream)))

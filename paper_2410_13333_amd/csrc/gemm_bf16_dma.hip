@@ -121,7 +121,13 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   const int nwg = gridDim.x, pid = blockIdx.x;
   const int xcd = pid & 7, q = nwg >> 3, rem = nwg & 7;
   const int tile = xcd * q + (xcd < rem ? xcd : rem) + (pid >> 3);
-  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
+  // inside its run an XCD walks groups of GM tile rows, N fastest within a group, so that the ~32 tiles it has in
+  // flight form a squarish patch and share both A and B panels in its L2
+  constexpr int GM = 4;
+  const int gm = GM < tiles_m ? GM : tiles_m;
+  const int per_group = gm * (nwg / tiles_m), grp = tile / per_group, first_m = grp * gm;
+  const int gsz = min(tiles_m - first_m, gm), in_grp = tile - grp * per_group;
+  const int m0 = (first_m + in_grp % gsz) * BM, n0 = (in_grp / gsz) * BN;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
 

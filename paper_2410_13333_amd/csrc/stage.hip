@@ -468,18 +468,22 @@ int mls_stage_timing_read(mls_stage* s, double* ms, int64_t* launches) {
   return MLS_OK;
 }
 
-int mls_gemm(int32_t dtype, int32_t mode, const void* A, const void* B, void* C, const void* R, int64_t M, int64_t N,
-             int64_t K, void* hip_stream) {
+int mls_gemm(int32_t dtype, int32_t mode, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+             const void* R, int64_t M, int64_t N, int64_t K, void* hip_stream) {
   if (!A || !B || !C) return fail(MLS_E_NULL, "mls_gemm: null argument");
   if (dtype != MLS_BF16 && dtype != MLS_FP32) return fail(MLS_E_CONFIG, "mls_gemm: bad dtype");
   if (mode < 0 || mode > 2) return fail(MLS_E_CONFIG, "mls_gemm: mode must be 0, 1 or 2");
   if (M < 0 || N < 0 || K < 0 || M % 8 || N % 8 || K % 8 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
     return fail(MLS_E_CONFIG, "mls_gemm: dimensions must be non-negative multiples of 8 below 2^24");
-  const int64_t lda = mode == mls::GEMM_TN ? M : K;
-  const int64_t ldb = mode == mls::GEMM_NT ? K : N;
+  const int64_t a_len = mode == mls::GEMM_TN ? M : K, b_len = mode == mls::GEMM_NT ? K : N;
+  if (lda == 0) lda = a_len;
+  if (ldb == 0) ldb = b_len;
+  if (ldc == 0) ldc = N;
+  if (lda < a_len || ldb < b_len || ldc < N || lda % 8 || ldb % 8 || ldc % 8)
+    return fail(MLS_E_CONFIG, "mls_gemm: a row stride must be a multiple of 8 not below the row length");
   hipStream_t st = (hipStream_t)hip_stream;
-  hipError_t e = dtype == MLS_BF16 ? mls::gemm_bf16(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, N, st)
-                                   : mls::gemm_f32(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, N, st);
+  hipError_t e = dtype == MLS_BF16 ? mls::gemm_bf16(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, st)
+                                   : mls::gemm_f32(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, st);
   if (e != hipSuccess) return fail_hip(e, "mls_gemm launch");
   return MLS_OK;
 }

@@ -86,11 +86,14 @@ def _stream(seed, tensor_id, layer):
 
 
 def normal(seed, tensor_id, layer, n, start=0):
-    """n standard normals (fp64) for flat indices start .. start+n-1 of tensor (tensor_id, layer)."""
+    """n standard normals (fp64) for flat indices start .. start+n-1 of tensor (tensor_id, layer).
+    Large requests are cut into chunks that a small thread pool fills (the value of an element depends on
+    its index only, never on the chunking)."""
     s = _stream(seed, tensor_id, layer)
     out = np.empty(n, dtype=np.float64)
-    chunk = 1 << 22
-    for lo in range(0, n, chunk):
+    chunk = 1 << 20
+
+    def fill(lo):
         hi = min(n, lo + chunk)
         i = np.arange(start + lo, start + hi, dtype=np.uint64)
         with np.errstate(over="ignore"):
@@ -100,6 +103,16 @@ def normal(seed, tensor_id, layer, n, start=0):
         u1 = ((r1 >> np.uint64(11)).astype(np.float64) + 1.0) * 2.0 ** -53
         u2 = (r2 >> np.uint64(11)).astype(np.float64) * 2.0 ** -53
         out[lo:hi] = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * np.pi) * u2)
+
+    starts = range(0, n, chunk)
+    if n <= 4 * chunk:
+        for lo in starts:
+            fill(lo)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        import os
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, starts))
     return out
 
 

@@ -33,8 +33,15 @@ def storage_bits(t):
     return t.cpu().numpy()
 
 
-def oracle_step(sh, wseed, xseed, dyseed, ks, params64=None):
-    """Oracle stage step with per-micro-batch layer counts ks.  Returns (ys, dxs, grads flat fp64 [max_layers*P])."""
+def bf16_store(name, t):
+    """store hook of the oracle's storage-rounded mode: every stored tensor is rounded once to bf16."""
+    _, v = synth.round_to_storage(np.ascontiguousarray(t).reshape(-1), "bf16")
+    return v.reshape(t.shape)
+
+
+def oracle_step(sh, wseed, xseed, dyseed, ks, params64=None, store=None):
+    """Oracle stage step with per-micro-batch layer counts ks.  Returns (ys, dxs, grads flat fp64 [max_layers*P]).
+    store: None = exact fp64 oracle; bf16_store = the oracle's storage-rounded mode."""
     if params64 is None:
         _, params64 = synth.make_params(sh, wseed)
     W = [synth.split_params(sh, params64, l) for l in range(sh.layers)]
@@ -44,8 +51,8 @@ def oracle_step(sh, wseed, xseed, dyseed, ks, params64=None):
     for mb, k in enumerate(ks):
         _, x = synth.make_x(sh, xseed, mb)
         _, dy = synth.make_dy(sh, dyseed, mb)
-        y, caches = O.stage_forward(x, W, sh, k)
-        dx, grads = O.stage_backward(dy, W[:k], caches, sh)
+        y, caches = O.stage_forward(x, W, sh, k, store)
+        dx, grads = O.stage_backward(dy, W[:k], caches, sh, store)
         for l in range(k):
             for name, tid, r, c, off in synth.param_layout(sh):
                 flat[l * per + off: l * per + off + r * c] += grads[l][name].reshape(-1)

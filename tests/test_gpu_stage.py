@@ -8,7 +8,8 @@ import numpy as np
 import pytest
 
 import synth
-from tests.helpers import (gpu_step, grad_errors, oracle_step, rel_err, storage_bits, to_device, to_host64)
+from tests.helpers import (bf16_store, gpu_step, grad_errors, oracle_step, rel_err, storage_bits, to_device,
+                           to_host64)
 
 pytestmark = pytest.mark.gpu
 
@@ -20,16 +21,23 @@ GQA128 = synth.StageShape(hidden=256, n_q_heads=4, n_kv_heads=1, head_dim=128, f
                           layers=1, microbatches=2)
 
 
+TOL_STORED = 1e-2   # bf16 run against the oracle in storage-rounded mode (every op consumes bf16-rounded inputs)
+
+
 def _check(sh, ks, tol, interleave=False):
     ys, dxs, g, st = gpu_step(sh, 1000, 2000, 3000, ks, interleave)
-    rys, rdxs, rg = oracle_step(sh, 1000, 2000, 3000, ks)
-    for mb in range(len(ks)):
-        assert rel_err(ys[mb], rys[mb]) <= tol, ("y", mb, rel_err(ys[mb], rys[mb]))
-        assert rel_err(dxs[mb], rdxs[mb]) <= tol, ("dx", mb, rel_err(dxs[mb], rdxs[mb]))
-    worst, errs = grad_errors(sh, g, rg, max(ks) if ks else 0)
-    assert worst <= tol, sorted(errs.items(), key=lambda kv: -kv[1])[:4]
     assert st.inflight == 0
     st.close()
+    refs = [("exact", tol, oracle_step(sh, 1000, 2000, 3000, ks))]
+    if sh.dtype == "bf16":
+        refs.append(("stored", TOL_STORED, oracle_step(sh, 1000, 2000, 3000, ks, store=bf16_store)))
+    for kind, t, (rys, rdxs, rg) in refs:
+        ey = max(rel_err(ys[mb], rys[mb]) for mb in range(len(ks)))
+        ex = max(rel_err(dxs[mb], rdxs[mb]) for mb in range(len(ks)))
+        worst, errs = grad_errors(sh, g, rg, max(ks) if ks else 0)
+        print(f"[{sh.dtype} h={sh.hidden} S={sh.seq} ks={ks}] vs {kind} oracle: y {ey:.2e} dx {ex:.2e} grads {worst:.2e}")
+        assert ey <= t and ex <= t, (kind, ey, ex)
+        assert worst <= t, (kind, sorted(errs.items(), key=lambda kv: -kv[1])[:4])
     return ys, dxs, g
 
 
