@@ -16,6 +16,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# HBM bytes per GEMM launch (average over the three GEMM kernels, which have equal launch counts), from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/stage_7b_4x4_hbm_traffic.txt:
+# (2.0 * 343392 KiB fetched + 1.0 * 112927 KiB written) * 1024.  Only valid for the default workload.
+PROFILED_GEMM_TRAFFIC = {"7b": 8.19e8}
 
 
 def cpu_baseline(sh):
@@ -114,7 +118,7 @@ def main():
         "tau_ms_per_layer_microbatch": ms / (K * M),
         "model_flops_per_step": flops_step,
         "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": PROFILED_GEMM_TRAFFIC.get(a.workload),
                      "flops_per_launch": gemm_flops_launch, "avg_launch_ms": gemm_ms / gemm_n},
         "kernel_classes": classes,
     }

@@ -391,3 +391,22 @@ def test_storage_rounded_mode_is_the_same_function_with_rounded_stores():
     # every stored tensor is exactly representable in bf16
     from synth import round_to_storage
     assert np.array_equal(round_to_storage(y2.reshape(-1), "bf16")[1], y2.reshape(-1))
+
+
+def test_oracle_regression_values_tiny_stage():
+    """Stored oracle outputs (written by tests/golden/make_golden.py, which calls only the oracle)."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    got = mod.values()
+    stored = {}
+    for line in open(os.path.join(here, "golden", "tiny_stage_fp64.txt")):
+        if not line.startswith("#"):
+            k, v = line.rstrip("\n").split("\t")
+            stored[k] = float(v)
+    assert set(got) == set(stored)
+    for k in stored:
+        assert math.isclose(got[k], stored[k], rel_tol=1e-9, abs_tol=1e-12), k
