@@ -147,15 +147,14 @@ __device__ __forceinline__ void store_t(bf16_t* __restrict__ out, int64_t ld, in
 // grid (n_q, q blocks of 128, b) with the longest query blocks dispatched first over all heads; wave w owns
 // query rows q0 + 32w .. +31; loops over KV blocks of 64.  Two workgroups fit a CU.
 template <int D>
-__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
-                                                              float* __restrict__ lse, int S, int nq, int nkv) {
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, int64_t ld, bf16_t* __restrict__ o, int64_t ldo,
+                                                                 float* __restrict__ lse, int S, int nq, int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][K|V]
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int qb = gridDim.y - 1 - blockIdx.y;  // longest rows first
   const int hq = blockIdx.x, bi = blockIdx.z, hk = hq / (nq / nkv);
-  const int64_t ld = int64_t(nq + 2 * nkv) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
   const float sc = rsqrtf((float)D) * LOG2E;
@@ -241,9 +240,9 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
   wait_dma();
   l += __shfl_xor(l, 32, 64);
   const float inv = 1.f / l;
-  bf16_t* ob = o + int64_t(bi) * S * (int64_t(nq) * D);
+  bf16_t* ob = o + int64_t(bi) * S * ldo;
 #pragma unroll
-  for (int t = 0; t < DT; t++) store_t(ob, int64_t(nq) * D, qi, hq * D + t * 32, acc[t], inv, lane, qi < S);
+  for (int t = 0; t < DT; t++) store_t(ob, ldo, qi, hq * D + t * 32, acc[t], inv, lane, qi < S);
   if (lane < 32 && qi < S) lse[(int64_t(bi) * nq + hq) * S + qi] = (m + __builtin_amdgcn_logf(l)) * LN2;
 }
 
@@ -251,18 +250,18 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
 // Same decomposition as the forward.  Per KV block: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - delta),
 // dQ^T += K^T dS^T.
 template <int D>
-__global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
-                                                             const bf16_t* __restrict__ d_o,
-                                                             const float* __restrict__ lse,
-                                                             const float* __restrict__ delta,
-                                                             bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv, int64_t ld,
+                                                                const bf16_t* __restrict__ d_o, int64_t ldo,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ delta,
+                                                                bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
+                                                                int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int qb = gridDim.y - 1 - blockIdx.y;
   const int hq = blockIdx.x, bi = blockIdx.z, hk = hq / (nq / nkv);
-  const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
   const int q0 = qb * 128, qw = q0 + wave * 32, qi = qw + (lane & 31);
@@ -335,9 +334,9 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
     }
   }
   wait_dma();
-  bf16_t* out = dqkv + int64_t(bi) * S * ld;
+  bf16_t* out = dqkv + int64_t(bi) * S * ldg;
 #pragma unroll
-  for (int t = 0; t < DT; t++) store_t(out, ld, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
+  for (int t = 0; t < DT; t++) store_t(out, ldg, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
 }
 
 // ================================================================ backward: dK, dV
@@ -345,18 +344,18 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
 // Loops over the query heads of the group and the query blocks of 64 rows at or below the diagonal:
 // S = Q K^T and dP = dO V^T (lane column = key row), dV^T += dO^T P, dK^T += Q^T dS.
 template <int D>
-__global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
-                                                              const bf16_t* __restrict__ d_o,
+__global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv, int64_t ld,
+                                                              const bf16_t* __restrict__ d_o, int64_t ldo,
                                                               const float* __restrict__ lse,
                                                               const float* __restrict__ delta,
-                                                              bf16_t* __restrict__ dqkv, int S, int nq, int nkv) {
+                                                              bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
+                                                              int nkv) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
   __shared__ float stat[2][2][TR];                                       // [buffer][lse*log2e | delta]
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kb = blockIdx.y, hk = blockIdx.x, bi = blockIdx.z, grp = nq / nkv;
-  const int64_t ld = int64_t(nq + 2 * nkv) * D, ldo = int64_t(nq) * D;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
   const int j0 = kb * 128, jw = j0 + wave * 32, ji = jw + (lane & 31);
@@ -445,11 +444,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
     if (it + 1 < niter) put_stat(it + 1);
   }
   wait_dma();
-  bf16_t* out = dqkv + int64_t(bi) * S * ld;
+  bf16_t* out = dqkv + int64_t(bi) * S * ldg;
 #pragma unroll
   for (int t = 0; t < DT; t++) {
-    store_t(out, ld, ji, (nq + hk) * D + t * 32, dk[t], scale, lane, ji < S);
-    store_t(out, ld, ji, (nq + nkv + hk) * D + t * 32, dv[t], 1.f, lane, ji < S);
+    store_t(out, ldg, ji, (nq + hk) * D + t * 32, dk[t], scale, lane, ji < S);
+    store_t(out, ldg, ji, (nq + nkv + hk) * D + t * 32, dv[t], 1.f, lane, ji < S);
   }
 }
 
@@ -457,47 +456,55 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
 
 namespace mls {
 
-hipError_t attn_fwd_bf16(const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
+hipError_t attn_fwd_bf16(const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o, float* lse, int b, int S, int nq, int nkv,
+                         int d, hipStream_t st) {
   if (b == 0 || S == 0) return hipSuccess;
   dim3 grid(nq, (S + 127) / 128, b);
   if (d == 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (bf16_t*)o, lse, S, nq, nkv);
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (bf16_t*)o, ld_o,
+                       lse, S, nq, nkv);
   else if (d == 64)
-    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (bf16_t*)o, lse, S, nq, nkv);
+    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (bf16_t*)o, ld_o,
+                       lse, S, nq, nkv);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-hipError_t attn_bwd_bf16(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                         int b, int S, int nq, int nkv, int d, hipStream_t st) {
+hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
+                         int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
+                         hipStream_t st) {
   if (b == 0 || S == 0) return hipSuccess;
-  hipError_t e = attn_delta(DT_BF16, o, d_o, delta, b, S, nq, d, st);
+  hipError_t e = attn_delta(DT_BF16, o, ld_o, d_o, ld_do, delta, b, S, nq, d, st);
   if (e != hipSuccess) return e;
   dim3 gq(nq, (S + 127) / 128, b), gk(nkv, (S + 127) / 128, b);
   if (d == 128) {
-    hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
-                       delta, (bf16_t*)dqkv, S, nq, nkv);
-    hipLaunchKernelGGL(attn_dkv_kernel<128>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
-                       delta, (bf16_t*)dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dkv_kernel<128>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
   } else if (d == 64) {
-    hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
-                       delta, (bf16_t*)dqkv, S, nq, nkv);
-    hipLaunchKernelGGL(attn_dkv_kernel<64>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, (const bf16_t*)d_o, lse,
-                       delta, (bf16_t*)dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL(attn_dkv_kernel<64>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
   } else {
     return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
-hipError_t attn_fwd(int dt, const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
-  return dt == DT_BF16 ? attn_fwd_bf16(qkv, o, lse, b, S, nq, nkv, d, st) : attn_fwd_f32(qkv, o, lse, b, S, nq, nkv, d, st);
+hipError_t attn_fwd(int dt, const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o, float* lse, int b, int S, int nq,
+                    int nkv, int d, hipStream_t st) {
+  return dt == DT_BF16 ? attn_fwd_bf16(qkv, ld_qkv, o, ld_o, lse, b, S, nq, nkv, d, st)
+                       : attn_fwd_f32(qkv, ld_qkv, o, ld_o, lse, b, S, nq, nkv, d, st);
 }
-hipError_t attn_bwd(int dt, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                    int b, int S, int nq, int nkv, int d, hipStream_t st) {
-  return dt == DT_BF16 ? attn_bwd_bf16(qkv, o, lse, d_o, dqkv, delta, b, S, nq, nkv, d, st)
-                       : attn_bwd_f32(qkv, o, lse, d_o, dqkv, delta, b, S, nq, nkv, d, st);
+hipError_t attn_bwd(int dt, const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse,
+                    const void* d_o, int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq,
+                    int nkv, int d, hipStream_t st) {
+  return dt == DT_BF16
+             ? attn_bwd_bf16(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st)
+             : attn_bwd_f32(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st);
 }
 
 }  // namespace mls

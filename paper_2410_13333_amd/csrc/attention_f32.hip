@@ -8,14 +8,13 @@ namespace {
 
 constexpr int DMAX = 128;
 
-__global__ __launch_bounds__(64) void attn_fwd_f32_kernel(const float* __restrict__ qkv, float* __restrict__ o,
-                                                          float* __restrict__ lse, int b, int S, int nq, int nkv,
-                                                          int d) {
+__global__ __launch_bounds__(64) void attn_fwd_f32_kernel(const float* __restrict__ qkv, int64_t ld,
+                                                          float* __restrict__ o, int64_t ldo, float* __restrict__ lse,
+                                                          int b, int S, int nq, int nkv, int d) {
   const int64_t id = int64_t(blockIdx.x) * 64 + threadIdx.x;
   if (id >= int64_t(b) * nq * S) return;
   const int i = int(id % S), hq = int((id / S) % nq), bi = int(id / (int64_t(S) * nq));
   const int hk = hq / (nq / nkv);
-  const int64_t ld = int64_t(nq + 2 * nkv) * d;
   const float* q = qkv + (int64_t(bi) * S + i) * ld + hq * d;
   const float* kb = qkv + int64_t(bi) * S * ld + int64_t(nq + hk) * d;
   const float* vb = kb + int64_t(nkv) * d;
@@ -35,14 +34,15 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(const float* __restric
     for (int c = 0; c < DMAX; c++) if (c < d) acc[c] = acc[c] * corr + p * vb[j * ld + c];
     m = mn;
   }
-  float* orow = o + (int64_t(bi) * S + i) * (int64_t(nq) * d) + hq * d;
+  float* orow = o + (int64_t(bi) * S + i) * ldo + hq * d;
 #pragma unroll
   for (int c = 0; c < DMAX; c++) if (c < d) orow[c] = acc[c] / l;
   lse[(int64_t(bi) * nq + hq) * S + i] = m + __logf(l);
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ o, const T* __restrict__ d_o,
+__global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ o, int64_t ldo,
+                                                         const T* __restrict__ d_o, int64_t ldd,
                                                          float* __restrict__ delta, int b, int S, int nq, int d) {
   // one wavefront per (token, head)
   const int64_t w = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 6;
@@ -50,27 +50,27 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ o
   if (w >= int64_t(b) * S * nq) return;
   const int hq = int(w % nq);
   const int64_t t = w / nq;
-  const T* po = o + t * (int64_t(nq) * d) + hq * d;
-  const T* pd = d_o + t * (int64_t(nq) * d) + hq * d;
+  const T* po = o + t * ldo + hq * d;
+  const T* pd = d_o + t * ldd + hq * d;
   float s = 0.f;
   for (int c = lane; c < d; c += 64) s += to_f32(po[c]) * to_f32(pd[c]);
   s = wave_sum(s);
   if (lane == 0) delta[(int64_t(t / S) * nq + hq) * S + (t % S)] = s;
 }
 
-__global__ __launch_bounds__(64) void attn_dq_f32_kernel(const float* __restrict__ qkv, const float* __restrict__ lse,
-                                                         const float* __restrict__ d_o,
-                                                         const float* __restrict__ delta, float* __restrict__ dqkv,
-                                                         int b, int S, int nq, int nkv, int d) {
+__global__ __launch_bounds__(64) void attn_dq_f32_kernel(const float* __restrict__ qkv, int64_t ld,
+                                                         const float* __restrict__ lse, const float* __restrict__ d_o,
+                                                         int64_t ldd, const float* __restrict__ delta,
+                                                         float* __restrict__ dqkv, int64_t ldg, int b, int S, int nq,
+                                                         int nkv, int d) {
   const int64_t id = int64_t(blockIdx.x) * 64 + threadIdx.x;
   if (id >= int64_t(b) * nq * S) return;
   const int i = int(id % S), hq = int((id / S) % nq), bi = int(id / (int64_t(S) * nq));
   const int hk = hq / (nq / nkv);
-  const int64_t ld = int64_t(nq + 2 * nkv) * d;
   const float* q = qkv + (int64_t(bi) * S + i) * ld + hq * d;
   const float* kb = qkv + int64_t(bi) * S * ld + int64_t(nq + hk) * d;
   const float* vb = kb + int64_t(nkv) * d;
-  const float* dor = d_o + (int64_t(bi) * S + i) * (int64_t(nq) * d) + hq * d;
+  const float* dor = d_o + (int64_t(bi) * S + i) * ldd + hq * d;
   const float scale = rsqrtf((float)d);
   const float L = lse[(int64_t(bi) * nq + hq) * S + i], D = delta[(int64_t(bi) * nq + hq) * S + i];
   float qr[DMAX], dr[DMAX], acc[DMAX];
@@ -85,20 +85,20 @@ __global__ __launch_bounds__(64) void attn_dq_f32_kernel(const float* __restrict
 #pragma unroll
     for (int c = 0; c < DMAX; c++) if (c < d) acc[c] += ds * kb[j * ld + c];
   }
-  float* out = dqkv + (int64_t(bi) * S + i) * ld + hq * d;
+  float* out = dqkv + (int64_t(bi) * S + i) * ldg + hq * d;
 #pragma unroll
   for (int c = 0; c < DMAX; c++) if (c < d) out[c] = acc[c];
 }
 
-__global__ __launch_bounds__(64) void attn_dkv_f32_kernel(const float* __restrict__ qkv, const float* __restrict__ lse,
-                                                          const float* __restrict__ d_o,
-                                                          const float* __restrict__ delta, float* __restrict__ dqkv,
-                                                          int b, int S, int nq, int nkv, int d) {
+__global__ __launch_bounds__(64) void attn_dkv_f32_kernel(const float* __restrict__ qkv, int64_t ld,
+                                                          const float* __restrict__ lse, const float* __restrict__ d_o,
+                                                          int64_t ldd, const float* __restrict__ delta,
+                                                          float* __restrict__ dqkv, int64_t ldg, int b, int S, int nq,
+                                                          int nkv, int d) {
   const int64_t id = int64_t(blockIdx.x) * 64 + threadIdx.x;
   if (id >= int64_t(b) * nkv * S) return;
   const int j = int(id % S), hk = int((id / S) % nkv), bi = int(id / (int64_t(S) * nkv));
   const int grp = nq / nkv;
-  const int64_t ld = int64_t(nq + 2 * nkv) * d;
   const float* kr_ = qkv + (int64_t(bi) * S + j) * ld + int64_t(nq + hk) * d;
   const float* vr_ = kr_ + int64_t(nkv) * d;
   const float scale = rsqrtf((float)d);
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(64) void attn_dkv_f32_kernel(const float* __restric
   for (int hq = hk * grp; hq < (hk + 1) * grp; hq++) {
     for (int i = j; i < S; i++) {
       const float* q = qkv + (int64_t(bi) * S + i) * ld + hq * d;
-      const float* dor = d_o + (int64_t(bi) * S + i) * (int64_t(nq) * d) + hq * d;
+      const float* dor = d_o + (int64_t(bi) * S + i) * ldd + hq * d;
       float s = 0.f, dp = 0.f;
 #pragma unroll
       for (int c = 0; c < DMAX; c++) if (c < d) { s += q[c] * kr[c]; dp += dor[c] * vr[c]; }
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(64) void attn_dkv_f32_kernel(const float* __restric
       for (int c = 0; c < DMAX; c++) if (c < d) { dv[c] += p * dor[c]; dk[c] += ds * q[c]; }
     }
   }
-  float* ok = dqkv + (int64_t(bi) * S + j) * ld + int64_t(nq + hk) * d;
+  float* ok = dqkv + (int64_t(bi) * S + j) * ldg + int64_t(nq + hk) * d;
   float* ov = ok + int64_t(nkv) * d;
 #pragma unroll
   for (int c = 0; c < DMAX; c++) if (c < d) { ok[c] = dk[c]; ov[c] = dv[c]; }
@@ -129,38 +129,40 @@ __global__ __launch_bounds__(64) void attn_dkv_f32_kernel(const float* __restric
 
 namespace mls {
 
-hipError_t attn_delta(int dt, const void* o, const void* d_o, float* delta, int b, int S, int nq, int d,
-                      hipStream_t st) {
+hipError_t attn_delta(int dt, const void* o, int64_t ld_o, const void* d_o, int64_t ld_do, float* delta, int b, int S,
+                      int nq, int d, hipStream_t st) {
   const int64_t waves = int64_t(b) * S * nq;
   if (waves == 0) return hipSuccess;
   const int blocks = int((waves * 64 + 255) / 256);
   if (dt == DT_BF16)
-    hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)o, (const bf16_t*)d_o,
-                       delta, b, S, nq, d);
+    hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)o, ld_o,
+                       (const bf16_t*)d_o, ld_do, delta, b, S, nq, d);
   else
-    hipLaunchKernelGGL(attn_delta_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)o, (const float*)d_o,
-                       delta, b, S, nq, d);
+    hipLaunchKernelGGL(attn_delta_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)o, ld_o,
+                       (const float*)d_o, ld_do, delta, b, S, nq, d);
   return hipGetLastError();
 }
 
-hipError_t attn_fwd_f32(const void* qkv, void* o, float* lse, int b, int S, int nq, int nkv, int d, hipStream_t st) {
+hipError_t attn_fwd_f32(const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o, float* lse, int b, int S, int nq, int nkv,
+                        int d, hipStream_t st) {
   const int64_t n = int64_t(b) * nq * S;
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(int((n + 63) / 64)), dim3(64), 0, st, (const float*)qkv, (float*)o, lse,
-                     b, S, nq, nkv, d);
+  hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(int((n + 63) / 64)), dim3(64), 0, st, (const float*)qkv, ld_qkv, (float*)o,
+                     ld_o, lse, b, S, nq, nkv, d);
   return hipGetLastError();
 }
 
-hipError_t attn_bwd_f32(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                        int b, int S, int nq, int nkv, int d, hipStream_t st) {
+hipError_t attn_bwd_f32(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
+                        int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
+                        hipStream_t st) {
   const int64_t n = int64_t(b) * nq * S, nk = int64_t(b) * nkv * S;
   if (n == 0) return hipSuccess;
-  hipError_t e = attn_delta(DT_FP32, o, d_o, delta, b, S, nq, d, st);
+  hipError_t e = attn_delta(DT_FP32, o, ld_o, d_o, ld_do, delta, b, S, nq, d, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_dq_f32_kernel, dim3(int((n + 63) / 64)), dim3(64), 0, st, (const float*)qkv, lse,
-                     (const float*)d_o, delta, (float*)dqkv, b, S, nq, nkv, d);
-  hipLaunchKernelGGL(attn_dkv_f32_kernel, dim3(int((nk + 63) / 64)), dim3(64), 0, st, (const float*)qkv, lse,
-                     (const float*)d_o, delta, (float*)dqkv, b, S, nq, nkv, d);
+  hipLaunchKernelGGL(attn_dq_f32_kernel, dim3(int((n + 63) / 64)), dim3(64), 0, st, (const float*)qkv, ld_qkv, lse,
+                     (const float*)d_o, ld_do, delta, (float*)dqkv, ld_dqkv, b, S, nq, nkv, d);
+  hipLaunchKernelGGL(attn_dkv_f32_kernel, dim3(int((nk + 63) / 64)), dim3(64), 0, st, (const float*)qkv, ld_qkv, lse,
+                     (const float*)d_o, ld_do, delta, (float*)dqkv, ld_dqkv, b, S, nq, nkv, d);
   return hipGetLastError();
 }
 

@@ -12,12 +12,13 @@ constexpr int EW_THREADS = 256;
 
 // ---------------------------------------------------------------- RMSNorm forward: one workgroup per row
 template <typename T, int NORM_MAXC>
-__global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
-                                                                 T* __restrict__ a, float* __restrict__ rstd, int h,
+__global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x, int64_t ldx,
+                                                                 const T* __restrict__ gamma, T* __restrict__ a,
+                                                                 int64_t lda, float* __restrict__ rstd, int h,
                                                                  float eps) {
   __shared__ float red[EW_THREADS / 64];
   const int64_t row = blockIdx.x;
-  const T* xr = x + row * h;
+  const T* xr = x + row * ldx;
   const int nchunk = h >> 3;
   float v[NORM_MAXC][8];
   float ss = 0.f;
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __rest
       load8(gamma + c * 8, g);
 #pragma unroll
       for (int e = 0; e < 8; e++) o[e] = v[i][e] * r * g[e];
-      store8(a + row * h + c * 8, o);
+      store8(a + row * lda + c * 8, o);
     }
   }
 }
@@ -49,10 +50,11 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __rest
 // Workgroup w handles rows w, w + gridDim.x, ...; it keeps its share of the column sums for dgamma in
 // registers and writes them to partial[w][:], which a second kernel adds up in a fixed order.
 template <typename T, int NORM_MAXC>
-__global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ da, const T* __restrict__ x,
+__global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ da, int64_t ld_da,
+                                                                 const T* __restrict__ x, int64_t ldx,
                                                                  const T* __restrict__ gamma,
-                                                                 const float* __restrict__ rstd,
-                                                                 const T* dres, T* dx,
+                                                                 const float* __restrict__ rstd, const T* dres,
+                                                                 int64_t ld_dres, T* dx, int64_t ld_dx,
                                                                  float* __restrict__ partial, int rows, int h) {
   __shared__ float red[EW_THREADS / 64];
   const int nchunk = h >> 3;
@@ -73,8 +75,8 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
       const int c = threadIdx.x + i * EW_THREADS;
       if (c < nchunk) {
         float xv[8], dav[8];
-        load8(x + row * h + c * 8, xv);
-        load8(da + row * h + c * 8, dav);
+        load8(x + row * ldx + c * 8, xv);
+        load8(da + row * ld_da + c * 8, dav);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           n[i][e] = xv[e] * r;
@@ -90,10 +92,10 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
       const int c = threadIdx.x + i * EW_THREADS;
       if (c < nchunk) {
         float res[8], o[8];
-        load8(dres + row * h + c * 8, res);
+        load8(dres + row * ld_dres + c * 8, res);
 #pragma unroll
         for (int e = 0; e < 8; e++) o[e] = res[e] + r * (dn[i][e] - n[i][e] * mean);
-        store8(dx + row * h + c * 8, o);
+        store8(dx + row * ld_dx + c * 8, o);
       }
     }
   }
@@ -150,41 +152,44 @@ __global__ __launch_bounds__(EW_THREADS) void rope_kernel(T* __restrict__ u, con
 __device__ __forceinline__ float sigmoidf_(float g) { return 1.f / (1.f + __expf(-g)); }
 
 template <typename T>
-__global__ __launch_bounds__(EW_THREADS) void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ z,
-                                                                int64_t total, int f) {
+__global__ __launch_bounds__(EW_THREADS) void swiglu_fwd_kernel(const T* __restrict__ gu, int64_t ld_gu,
+                                                                T* __restrict__ z, int64_t ld_z, int64_t total,
+                                                                int f) {
   const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
   if (id >= total) return;
   const int cpr = f >> 3;
   const int64_t t = id / cpr;
   const int c = int(id % cpr);
   float g[8], u[8], o[8];
-  load8(gu + t * 2 * f + c * 8, g);
-  load8(gu + t * 2 * f + f + c * 8, u);
+  load8(gu + t * ld_gu + c * 8, g);
+  load8(gu + t * ld_gu + f + c * 8, u);
 #pragma unroll
   for (int e = 0; e < 8; e++) o[e] = g[e] * sigmoidf_(g[e]) * u[e];
-  store8(z + t * f + c * 8, o);
+  store8(z + t * ld_z + c * 8, o);
 }
 
 template <typename T>
-__global__ __launch_bounds__(EW_THREADS) void swiglu_bwd_kernel(const T* __restrict__ dz, const T* __restrict__ gu,
-                                                                T* __restrict__ dgu, int64_t total, int f) {
+__global__ __launch_bounds__(EW_THREADS) void swiglu_bwd_kernel(const T* __restrict__ dz, int64_t ld_dz,
+                                                                const T* __restrict__ gu, int64_t ld_gu,
+                                                                T* __restrict__ dgu, int64_t ld_dgu, int64_t total,
+                                                                int f) {
   const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
   if (id >= total) return;
   const int cpr = f >> 3;
   const int64_t t = id / cpr;
   const int c = int(id % cpr);
   float g[8], u[8], d[8], og[8], ou[8];
-  load8(gu + t * 2 * f + c * 8, g);
-  load8(gu + t * 2 * f + f + c * 8, u);
-  load8(dz + t * f + c * 8, d);
+  load8(gu + t * ld_gu + c * 8, g);
+  load8(gu + t * ld_gu + f + c * 8, u);
+  load8(dz + t * ld_dz + c * 8, d);
 #pragma unroll
   for (int e = 0; e < 8; e++) {
     const float s = sigmoidf_(g[e]);
     og[e] = d[e] * u[e] * s * (1.f + g[e] * (1.f - s));
     ou[e] = d[e] * g[e] * s;
   }
-  store8(dgu + t * 2 * f + c * 8, og);
-  store8(dgu + t * 2 * f + f + c * 8, ou);
+  store8(dgu + t * ld_dgu + c * 8, og);
+  store8(dgu + t * ld_dgu + f + c * 8, ou);
 }
 
 // ---------------------------------------------------------------- weight generator (counter-based, fp64 Box-Muller)
@@ -210,16 +215,17 @@ __device__ __forceinline__ void put(bf16_t* p, double v) { *reinterpret_cast<uin
 __device__ __forceinline__ void put(float* p, double v) { *p = (float)v; }
 
 template <typename T>
-__global__ __launch_bounds__(EW_THREADS) void fill_normal_kernel(T* __restrict__ out, int64_t n, uint64_t stream,
-                                                                 double scale, double offset) {
-  const int64_t i = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+__global__ __launch_bounds__(EW_THREADS) void fill_normal_kernel(T* __restrict__ out, int64_t n, int64_t cols,
+                                                                 int64_t ld, uint64_t stream, double scale,
+                                                                 double offset) {
+  const int64_t i = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;  // flat index in the dense (public) layout
   if (i >= n) return;
   const uint64_t c = stream + 2ull * (uint64_t)i;
   const uint64_t r1 = mix64(c), r2 = mix64(c + 1);
   const double u1 = ((double)(r1 >> 11) + 1.0) * 0x1p-53;
   const double u2 = (double)(r2 >> 11) * 0x1p-53;
   const double z = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
-  put(out + i, offset + scale * z);
+  put(out + (i / cols) * ld + (i % cols), offset + scale * z);
 }
 
 inline int blocks_for(int64_t n) { return int((n + EW_THREADS - 1) / EW_THREADS); }
@@ -228,12 +234,12 @@ inline int blocks_for(int64_t n) { return int((n + EW_THREADS - 1) / EW_THREADS)
 
 namespace mls {
 
-hipError_t rmsnorm_fwd(int dt, const void* x, const void* gamma, void* a, float* r, int T, int h, float eps,
-                       hipStream_t st) {
+hipError_t rmsnorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, void* a, int64_t lda, float* r, int T,
+                       int h, float eps, hipStream_t st) {
   if (T == 0) return hipSuccess;
 #define FWD(TY, C)                                                                                             \
-  hipLaunchKernelGGL((rmsnorm_fwd_kernel<TY, C>), dim3(T), dim3(EW_THREADS), 0, st, (const TY*)x, (const TY*)gamma, \
-                     (TY*)a, r, h, eps)
+  hipLaunchKernelGGL((rmsnorm_fwd_kernel<TY, C>), dim3(T), dim3(EW_THREADS), 0, st, (const TY*)x, ldx,             \
+                     (const TY*)gamma, (TY*)a, lda, r, h, eps)
   const int mc = h <= 4096 ? 2 : h <= 8192 ? 4 : 8;
   if (dt == DT_BF16) {
     if (mc == 2) FWD(bf16_t, 2); else if (mc == 4) FWD(bf16_t, 4); else FWD(bf16_t, 8);
@@ -246,13 +252,14 @@ hipError_t rmsnorm_fwd(int dt, const void* x, const void* gamma, void* a, float*
 
 int rmsnorm_bwd_blocks(int T) { return T < 512 ? (T > 0 ? T : 1) : 512; }
 
-hipError_t rmsnorm_bwd(int dt, const void* da, const void* x, const void* gamma, const float* r, const void* dres,
-                       void* dx, float* dgamma, float* partial, int T, int h, hipStream_t st) {
+hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
+                       const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
+                       float* partial, int T, int h, hipStream_t st) {
   if (T == 0) return hipSuccess;
   const int nb = rmsnorm_bwd_blocks(T);
 #define BWD(TY, C)                                                                                               \
-  hipLaunchKernelGGL((rmsnorm_bwd_kernel<TY, C>), dim3(nb), dim3(EW_THREADS), 0, st, (const TY*)da, (const TY*)x,     \
-                     (const TY*)gamma, r, (const TY*)dres, (TY*)dx, partial, T, h)
+  hipLaunchKernelGGL((rmsnorm_bwd_kernel<TY, C>), dim3(nb), dim3(EW_THREADS), 0, st, (const TY*)da, ld_da,            \
+                     (const TY*)x, ldx, (const TY*)gamma, r, (const TY*)dres, ld_dres, (TY*)dx, ld_dx, partial, T, h)
   const int mc = h <= 4096 ? 2 : h <= 8192 ? 4 : 8;
   if (dt == DT_BF16) {
     if (mc == 2) BWD(bf16_t, 2); else if (mc == 4) BWD(bf16_t, 4); else BWD(bf16_t, 8);
@@ -279,32 +286,34 @@ hipError_t rope_inplace(int dt, void* u, const float* cos_tab, const float* sin_
   return hipGetLastError();
 }
 
-hipError_t swiglu_fwd(int dt, const void* gu, void* z, int T, int f, hipStream_t st) {
+hipError_t swiglu_fwd(int dt, const void* gu, int64_t ld_gu, void* z, int64_t ld_z, int T, int f, hipStream_t st) {
   const int64_t total = int64_t(T) * (f >> 3);
   if (total == 0) return hipSuccess;
   if (dt == DT_BF16)
     hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)gu,
-                       (bf16_t*)z, total, f);
+                       ld_gu, (bf16_t*)z, ld_z, total, f);
   else
     hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const float*)gu,
-                       (float*)z, total, f);
+                       ld_gu, (float*)z, ld_z, total, f);
   return hipGetLastError();
 }
 
-hipError_t swiglu_bwd(int dt, const void* dz, const void* gu, void* dgu, int T, int f, hipStream_t st) {
+hipError_t swiglu_bwd(int dt, const void* dz, int64_t ld_dz, const void* gu, int64_t ld_gu, void* dgu, int64_t ld_dgu,
+                      int T, int f, hipStream_t st) {
   const int64_t total = int64_t(T) * (f >> 3);
   if (total == 0) return hipSuccess;
   if (dt == DT_BF16)
     hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)dz,
-                       (const bf16_t*)gu, (bf16_t*)dgu, total, f);
+                       ld_dz, (const bf16_t*)gu, ld_gu, (bf16_t*)dgu, ld_dgu, total, f);
   else
     hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const float*)dz,
-                       (const float*)gu, (float*)dgu, total, f);
+                       ld_dz, (const float*)gu, ld_gu, (float*)dgu, ld_dgu, total, f);
   return hipGetLastError();
 }
 
-hipError_t fill_normal(int dt, void* out, int64_t n, uint64_t seed, uint32_t tensor, uint32_t layer, double scale,
-                       double offset, hipStream_t st) {
+hipError_t fill_normal(int dt, void* out, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, uint32_t tensor,
+                       uint32_t layer, double scale, double offset, hipStream_t st) {
+  const int64_t n = rows * cols;
   if (n == 0) return hipSuccess;
   auto mixh = [](uint64_t z) {
     z += 0x9E3779B97F4A7C15ull;
@@ -314,11 +323,11 @@ hipError_t fill_normal(int dt, void* out, int64_t n, uint64_t seed, uint32_t ten
   };
   const uint64_t stream = mixh(mixh(seed) ^ ((uint64_t(tensor) << 32) | layer));
   if (dt == DT_BF16)
-    hipLaunchKernelGGL(fill_normal_kernel<bf16_t>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (bf16_t*)out, n,
-                       stream, scale, offset);
+    hipLaunchKernelGGL(fill_normal_kernel<bf16_t>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (bf16_t*)out, n, cols,
+                       ld, stream, scale, offset);
   else
-    hipLaunchKernelGGL(fill_normal_kernel<float>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (float*)out, n, stream,
-                       scale, offset);
+    hipLaunchKernelGGL(fill_normal_kernel<float>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (float*)out, n, cols, ld,
+                       stream, scale, offset);
   return hipGetLastError();
 }
 

@@ -81,8 +81,8 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool ATR, bool BTR, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, void* __restrict__ Cv,
                                                                    const bf16_t* __restrict__ R, int M, int N, int K,
-                                                                   int64_t lda, int64_t ldb, int64_t ldc, int tiles_m,
-                                                                   int tiles_n) {
+                                                                   int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr,
+                                                                   int tiles_m, int tiles_n) {
   using G = Geo<BM, BN, BK, WGM, WGN, ATR, BTR>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
           const int64_t off = int64_t(row) * ldc + col;
           float v = acc[i][j][g * 4 + r];
           if (EPI == EPI_BF16) {
-            if (R) v += to_f32(R[off]);
+            if (R) v += to_f32(R[int64_t(row) * ldr + col]);
             reinterpret_cast<bf16_t*>(Cv)[off] = (bf16_t)v;
           } else {
             float* C = reinterpret_cast<float*>(Cv);
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool ATR, bool BTR, int EPI>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                  int64_t ldb, int64_t ldc, hipStream_t st) {
+                  int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   using G = Geo<BM, BN, BK, WGM, WGN, ATR, BTR>;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, ATR, BTR, EPI>;
   static bool attr_set = false;  // raising the dynamic LDS limit is a per-function, once-only call
@@ -186,16 +186,16 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
     attr_set = true;
   }
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(G::NT), G::LDS_BYTES, st, A, B, C, R, M, N, K, lda, ldb, ldc, tm, tn);
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(G::NT), G::LDS_BYTES, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, tm, tn);
   return hipGetLastError();
 }
 
 template <bool ATR, bool BTR, int EPI>
 hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                    int64_t ldb, int64_t ldc, hipStream_t st) {
+                    int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192) return launch<256, 256, 32, 2, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, st);
-  return launch<128, 128, 32, 2, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, st);
+  if (big_tiles >= 192) return launch<256, 256, 32, 2, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, st);
+  return launch<128, 128, 32, 2, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, st);
 }
 
 }  // namespace
@@ -203,16 +203,16 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
 namespace mls {
 
 hipError_t gemm_bf16(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
-                     int64_t ldb, int64_t ldc, hipStream_t st) {
+                     int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* b = static_cast<const bf16_t*>(B);
   const bf16_t* r = static_cast<const bf16_t*>(R);
   if (M == 0 || N == 0) return hipSuccess;
-  if (gemm_bf16_dma_ok(mode, M, N, K, lda, ldb)) return gemm_bf16_dma(mode, A, B, C, R, M, N, K, lda, ldb, ldc, st);
+  if (gemm_bf16_dma_ok(mode, M, N, K, lda, ldb)) return gemm_bf16_dma(mode, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, st);
   switch (mode) {
-    case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, st);
-    case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, st);
-    case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, st);
+    case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, st);
+    case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, st);
+    case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, st);
   }
   return hipErrorInvalidValue;
 }

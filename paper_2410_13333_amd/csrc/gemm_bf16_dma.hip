@@ -9,7 +9,9 @@
 //   [k][col] tiles (contraction index strided in memory), read with ds_read_b64_tr_b16:
 //        16-byte chunk c of k-row r lives in chunk c ^ ((r & 3) << 2)   (moves 64-byte blocks)
 // The pipeline keeps NS tile stages in LDS with ONE workgroup barrier per k-step: the loads of tile kt+NS-1 are
-// issued right after the barrier that publishes tile kt and retires the reads of tile kt-1.
+// issued right after the barrier that publishes tile kt and retires the reads of tile kt-1.  In the skewed
+// form (NS >= 3) that barrier already publishes tile kt+1, whose first fragments are then fetched during the
+// last substep of tile kt, so no LDS latency is exposed behind the barrier.
 // The LDS-DMA instructions are inline asm because the compiler would otherwise wait for all of them
 // (vmcnt(0)) before every LDS read; the waits are placed by hand.
 #include "common.h"
@@ -104,11 +106,11 @@ struct ColTile {
   }
 };
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                        void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-                                                       uint32_t a_bytes, uint32_t b_bytes, int tiles_m) {
+                                                       int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m) {
   using AT_R = RowTile<BM, BK>;
   using AT_C = ColTile<BM, BK>;
   using BT_R = RowTile<BN, BK>;
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   if (BTR) btc.init(n0, N, ldb, wave, lane); else btr.init(n0, N, ldb, wave, lane);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS unsigned char*)smem;
   const uint32_t a_wave = lds0 + wave * (A_BYTES / 4), b_wave = lds0 + A_BYTES + wave * (B_BYTES / 4);
-  constexpr int NIA = ATR ? AT_C::NI : AT_R::NI, NIB = BTR ? BT_C::NI : BT_R::NI;
+  constexpr int NIA = ATR ? AT_C::NI : AT_R::NI;
   // DMA instruction d (0 .. LPT-1) of this wave for k-tile kt into `stage`: the first NIA belong to A
   // (`live` false: the tile does not exist; the load is sent out of range and only zero-fills a dead stage, which
   // keeps the number of loads per k-step, and with it the vmcnt bookkeeping, constant and the loop branch-free)
@@ -173,48 +175,81 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   // LDS reads per 16-wide k-substep and the MFMA : read interleave the scheduler is asked for
   constexpr int NR = (ATR ? 2 : 1) * TM + (BTR ? 2 : 1) * TN, NMFMA = TM * TN;
   constexpr int DPK = (LPT + KS - 1) / KS;  // DMA instructions fired per k-substep
-  int stage = 0;
-  for (int kt = 0; kt < nk; kt++) {
-    // tile kt has landed once at most the loads of the NS-2 younger tiles are still in flight
-    wait_vmcnt<(NS - 2) * LPT>();
-    __syncthreads();
-    const bool prefetch = kt + NS - 1 < nk;
-    const int pstage = stage == 0 ? NS - 1 : stage - 1;
-    const unsigned char* sa = smem + stage * STAGE;
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto lfrag = [&](const unsigned char* sa, int kk, int buf) {
     const unsigned char* sb = sa + A_BYTES;
-    bf16x8 af[2][TM], bfr[2][TN];
-    auto lfrag = [&](int kk, int buf) {
 #pragma unroll
-      for (int i = 0; i < TM; i++)
-        af[buf][i] = ATR ? AT_C::frag(sa, wm + i * 32, kk, lane) : AT_R::frag(sa, wm + i * 32, kk, lane);
+    for (int i = 0; i < TM; i++)
+      af[buf][i] = ATR ? AT_C::frag(sa, wm + i * 32, kk, lane) : AT_R::frag(sa, wm + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+      bfr[buf][j] = BTR ? BT_C::frag(sb, wn + j * 32, kk, lane) : BT_R::frag(sb, wn + j * 32, kk, lane);
+  };
+  // one 16-wide k-substep: fire this substep's share of the next tile's DMA between the two halves of the MFMA
+  // block (operands swapped: the lane ends up with 4 consecutive columns of one row)
+  auto mfma_block = [&](int kk, int kt, int pstage, bool prefetch) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      if (i == TM / 2) {
+#pragma unroll
+        for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, kt + NS - 1, pstage, prefetch);
+      }
 #pragma unroll
       for (int j = 0; j < TN; j++)
-        bfr[buf][j] = BTR ? BT_C::frag(sb, wn + j * 32, kk, lane) : BT_R::frag(sb, wn + j * 32, kk, lane);
-    };
-    lfrag(0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+    }
+  };
+  auto interleave_hint = [&]() {  // spread the LDS reads just issued over the first half of the MFMAs
+    if (NMFMA >= 16) {
 #pragma unroll
-    for (int kk = 0; kk < KS; kk++) {
-      __builtin_amdgcn_sched_barrier(0);
-      if (kk + 1 < KS) lfrag(kk + 1, (kk + 1) & 1);
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        if (i == TM / 2) {  // the next tile's DMA goes out between the two halves of the MFMA block
-#pragma unroll
-          for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, kt + NS - 1, pstage, prefetch);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; j++)  // operands swapped: the lane ends up with 4 consecutive columns of one row
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-      }
-      if (kk + 1 < KS && NMFMA >= 16) {  // spread the next substep's LDS reads over the first half of the MFMAs
-#pragma unroll
-        for (int g = 0; g < NMFMA / 2; g++) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // 1 MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, NR / (NMFMA / 2), 0);  // its share of the DS reads
-        }
+      for (int g = 0; g < NMFMA / 2; g++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, NR / (NMFMA / 2), 0);  // its share of the DS reads
       }
     }
-    stage = stage + 1 == NS ? 0 : stage + 1;
+  };
+  int stage = 0;
+  if (SKEW) {
+    // Skewed pipeline (needs NS >= 3 and an even number of substeps): the barrier at the top of iteration kt
+    // publishes tile kt+1, so the first fragments of tile kt+1 are fetched during the last substep of tile kt
+    // and no LDS latency is exposed behind the barrier.
+    static_assert(!SKEW || (NS >= 3 && KS % 2 == 0), "skewed pipeline needs 3 stages");
+    wait_vmcnt<(NS - 2) * LPT>();
+    __syncthreads();
+    lfrag(smem, 0, 0);
+    for (int kt = 0; kt < nk; kt++) {
+      wait_vmcnt<(NS >= 3 ? NS - 3 : 0) * LPT>();  // this wave's part of tile kt+1 has landed
+      __syncthreads();                             // ... everyone's has; the reads of tile kt-1 are retired
+      const bool prefetch = kt + NS - 1 < nk;
+      const int pstage = stage == 0 ? NS - 1 : stage - 1, nstage = stage + 1 == NS ? 0 : stage + 1;
+      const unsigned char* sa = smem + stage * STAGE;
+#pragma unroll
+      for (int kk = 0; kk < KS; kk++) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1); else lfrag(smem + nstage * STAGE, 0, 0);
+        mfma_block(kk, kt, pstage, prefetch);
+        interleave_hint();
+      }
+      stage = nstage;
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt++) {
+      // tile kt has landed once at most the loads of the NS-2 younger tiles are still in flight
+      wait_vmcnt<(NS - 2) * LPT>();
+      __syncthreads();
+      const bool prefetch = kt + NS - 1 < nk;
+      const int pstage = stage == 0 ? NS - 1 : stage - 1;
+      const unsigned char* sa = smem + stage * STAGE;
+      lfrag(sa, 0, 0);
+#pragma unroll
+      for (int kk = 0; kk < KS; kk++) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1);
+        mfma_block(kk, kt, pstage, prefetch);
+        if (kk + 1 < KS) interleave_hint();
+      }
+      stage = stage + 1 == NS ? 0 : stage + 1;
+    }
   }
   wait_vmcnt<0>();  // nothing of this wave may still be writing LDS when it leaves
 
@@ -233,7 +268,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
         float v[4] = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
         if (EPI == EPI_BF16) {
           if (R) {
-            const uint2 rr = *reinterpret_cast<const uint2*>(R + off);
+            const uint2 rr = *reinterpret_cast<const uint2*>(R + int64_t(row) * ldr + col);
             v[0] += __uint_as_float(rr.x << 16);
             v[1] += __uint_as_float(rr.x & 0xffff0000u);
             v[2] += __uint_as_float(rr.y << 16);
@@ -253,11 +288,11 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   }
 }
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW = false>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                  int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
+                  int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
-  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI>;
+  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, SKEW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -265,16 +300,19 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
     attr_set = true;
   }
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, tm);
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm);
   return hipGetLastError();
 }
 
 template <bool ATR, bool BTR, int EPI>
 hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                    int64_t ldb, int64_t ldc, uint32_t ab, uint32_t bb, hipStream_t st) {
+                    int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192) return launch<256, 256, 64, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ab, bb, st);
-  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ab, bb, st);
+  // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
+  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.
+  if (big_tiles >= 192 && BTR) return launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+  if (big_tiles >= 192) return launch<256, 256, 64, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
 }
 
 }  // namespace
@@ -290,7 +328,7 @@ bool gemm_bf16_dma_ok(int mode, int M, int N, int K, int64_t lda, int64_t ldb) {
 }
 
 hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
-                         int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st) {
+                         int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* b = static_cast<const bf16_t*>(B);
   const bf16_t* r = static_cast<const bf16_t*>(R);
@@ -298,9 +336,9 @@ hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const 
   const int64_t a_rows = mode == GEMM_TN ? K : M, b_rows = mode == GEMM_NT ? N : K;
   const uint32_t ab = uint32_t(a_rows * lda * 2), bb = uint32_t(b_rows * ldb * 2);
   switch (mode) {
-    case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
-    case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
-    case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, ab, bb, st);
+    case GEMM_NN: return dispatch<false, true, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+    case GEMM_NT: return dispatch<false, false, EPI_BF16>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+    case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
   }
   return hipErrorInvalidValue;
 }

@@ -11,7 +11,7 @@ constexpr int FB = 64, FK = 16;
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                        float* C, const float* R, int M, int N, int K, int64_t sam,
                                                        int64_t sak, int64_t sbk, int64_t sbn, int64_t ldc,
-                                                       int accumulate) {
+                                                       int64_t ldr, int accumulate) {
   __shared__ float As[FK][FB + 1], Bs[FK][FB + 1];
   const int m0 = blockIdx.y * FB, n0 = blockIdx.x * FB;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
         const int64_t off = int64_t(row) * ldc + col;
         float v = acc[i][j];
         if (accumulate) v += C[off];
-        else if (R) v += R[off];
+        else if (R) v += R[int64_t(row) * ldr + col];
         C[off] = v;
       }
     }
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 namespace mls {
 
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
-                    int64_t ldb, int64_t ldc, hipStream_t st) {
+                    int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   if (M == 0 || N == 0) return hipSuccess;
   int64_t sam, sak, sbk, sbn;
   int acc = 0;
@@ -70,7 +70,7 @@ hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void*
   }
   dim3 grid((N + FB - 1) / FB, (M + FB - 1) / FB);
   hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, (const float*)A, (const float*)B, (float*)C,
-                     (const float*)R, M, N, K, sam, sak, sbk, sbn, ldc, acc);
+                     (const float*)R, M, N, K, sam, sak, sbk, sbn, ldc, ldr, acc);
   return hipGetLastError();
 }
 

@@ -77,9 +77,14 @@ struct mls_stage {
   size_t es;      // bytes per stored element
   int T, qd, kvd, qkvw;
   hipStream_t st;
-  size_t layer_params;  // elements per layer
-  size_t off_g1, off_wqkv, off_wo, off_g2, off_wgu, off_wd;
-  char* params = nullptr;  // storage type, public layout
+  size_t layer_params;  // elements per layer, public (dense) layout
+  size_t off_g1, off_wqkv, off_wo, off_g2, off_wgu, off_wd;  // public offsets (also the layout of grads)
+  // Internal row strides (elements).  Widths whose byte size is a multiple of 512 get 64 extra elements so that
+  // the rows of a GEMM tile do not all fall on the same L2 / memory channel.
+  int64_t ld_h, ld_qkv, ld_qd, ld_gu, ld_f;
+  size_t ilayer_params;  // elements per layer, internal (row-padded) layout
+  size_t ioff_g1, ioff_wqkv, ioff_wo, ioff_g2, ioff_wgu, ioff_wd;
+  char* params = nullptr;  // storage type, internal layout
   float *cos_tab = nullptr, *sin_tab = nullptr;
   LayerStash ls;
   char* stash = nullptr;  // [max_inflight][max_layers] LayerStash
@@ -90,12 +95,13 @@ struct mls_stage {
        *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr;
   const void* last_dy = nullptr;
+  int64_t last_dy_ld = 0;
   Timing tm;
 
   char* slot_layer(int slot, int layer) const {
     return stash + (size_t(slot) * c.max_layers + layer) * ls.bytes;
   }
-  char* param(int layer, size_t off) const { return params + (size_t(layer) * layer_params + off) * es; }
+  char* param(int layer, size_t ioff) const { return params + (size_t(layer) * ilayer_params + ioff) * es; }
 };
 
 namespace {
@@ -111,9 +117,9 @@ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
   } while (0)
 
 hipError_t gemm(const mls_stage* s, int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
-                int64_t lda, int64_t ldb, int64_t ldc) {
-  return s->dt == mls::DT_BF16 ? mls::gemm_bf16(mode, A, B, C, R, M, N, K, lda, ldb, ldc, s->st)
-                               : mls::gemm_f32(mode, A, B, C, R, M, N, K, lda, ldb, ldc, s->st);
+                int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr = 0) {
+  return s->dt == mls::DT_BF16 ? mls::gemm_bf16(mode, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, s->st)
+                               : mls::gemm_f32(mode, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, s->st);
 }
 
 int check_config(const mls_config& c) {
@@ -133,70 +139,92 @@ int check_config(const mls_config& c) {
   const int64_t widest = std::max<int64_t>(2 * int64_t(c.ffn), int64_t(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
   if (T > (1 << 24) || widest > (1 << 24) || T * widest > (int64_t(1) << 40))
     return fail(MLS_E_CONFIG, "tokens per micro-batch or layer width too large");
-  if (c.dtype == MLS_BF16 && int64_t(c.seq + 128) * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 2 >= (int64_t(1) << 31))
+  if (c.dtype == MLS_BF16 && int64_t(c.seq + 128) * ((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim + 64) * 2 >= (int64_t(1) << 31))
     return fail(MLS_E_CONFIG, "seq * (q_dim + 2 kv_dim) must stay below 2^30 elements for bf16 storage");
   return MLS_OK;
 }
 
-int init_weights(mls_stage* s, uint64_t seed) {
+int64_t padded(int64_t n) { return n % 256 == 0 ? n + 64 : n; }
+
+// the six parameter tensors of a layer: public offset, internal offset, rows, cols, internal row stride
+struct PTensor { size_t off, ioff; int64_t rows, cols, ld; uint32_t tid; double scale, offset; };
+void param_tensors(const mls_stage* s, PTensor (&t)[6]) {
   const mls_config& c = s->c;
-  for (int l = 0; l < c.max_layers; l++) {
-    struct { size_t off; int64_t n; uint32_t tid; double scale, offset; } t[6] = {
-        {s->off_g1, c.hidden, MLS_P_GAMMA1, 0.02, 1.0},
-        {s->off_wqkv, int64_t(c.hidden) * s->qkvw, MLS_P_WQKV, 0.02, 0.0},
-        {s->off_wo, int64_t(s->qd) * c.hidden, MLS_P_WO, 0.02, 0.0},
-        {s->off_g2, c.hidden, MLS_P_GAMMA2, 0.02, 1.0},
-        {s->off_wgu, int64_t(c.hidden) * 2 * c.ffn, MLS_P_WGU, 0.02, 0.0},
-        {s->off_wd, int64_t(c.ffn) * c.hidden, MLS_P_WD, 0.02, 0.0}};
-    for (auto& e : t) HIP_TRY(mls::fill_normal(s->dt, s->param(l, e.off), e.n, seed, e.tid, (uint32_t)l, e.scale, e.offset, s->st));
-  }
+  t[0] = {s->off_g1, s->ioff_g1, 1, c.hidden, c.hidden, MLS_P_GAMMA1, 0.02, 1.0};
+  t[1] = {s->off_wqkv, s->ioff_wqkv, c.hidden, s->qkvw, s->ld_qkv, MLS_P_WQKV, 0.02, 0.0};
+  t[2] = {s->off_wo, s->ioff_wo, s->qd, c.hidden, s->ld_h, MLS_P_WO, 0.02, 0.0};
+  t[3] = {s->off_g2, s->ioff_g2, 1, c.hidden, c.hidden, MLS_P_GAMMA2, 0.02, 1.0};
+  t[4] = {s->off_wgu, s->ioff_wgu, c.hidden, 2 * int64_t(c.ffn), s->ld_gu, MLS_P_WGU, 0.02, 0.0};
+  t[5] = {s->off_wd, s->ioff_wd, c.ffn, c.hidden, s->ld_h, MLS_P_WD, 0.02, 0.0};
+}
+
+int init_weights(mls_stage* s, uint64_t seed) {
+  PTensor t[6];
+  param_tensors(s, t);
+  for (int l = 0; l < s->c.max_layers; l++)
+    for (auto& e : t)
+      HIP_TRY(mls::fill_normal(s->dt, s->param(l, e.ioff), e.rows, e.cols, e.ld, seed, e.tid, (uint32_t)l, e.scale,
+                               e.offset, s->st));
   return MLS_OK;
+}
+
+// dense <-> row-padded copies of a rows x cols matrix of the storage type
+hipError_t copy2d(const mls_stage* s, void* dst, int64_t ld_dst, const void* src, int64_t ld_src, int64_t rows,
+                  int64_t cols) {
+  return hipMemcpy2DAsync(dst, size_t(ld_dst) * s->es, src, size_t(ld_src) * s->es, size_t(cols) * s->es, size_t(rows),
+                          hipMemcpyDeviceToDevice, s->st);
 }
 
 // ---- one decoder layer, forward.  `x` lives in the stash entry already; `out` receives x + attention + MLP.
-int layer_forward(mls_stage* s, int layer, char* e, void* out) {
+int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn;
-  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.x, s->param(layer, s->off_g1), e + L.a, (float*)(e + L.r1), T, h, c.rms_eps, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->off_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, h, s->qkvw, s->qkvw));
-  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim,
-                            s->qkvw, 1.f, s->st));
-  LAUNCH(CLS_ATTN_FWD, mls::attn_fwd(s->dt, e + L.qkv, e + L.o, (float*)(e + L.lse), c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads,
-                        c.head_dim, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->off_wo), e + L.h, e + L.x, T, h, s->qd, s->qd, h, h));
-  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.h, s->param(layer, s->off_g2), e + L.b, (float*)(e + L.r2), T, h, c.rms_eps, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->off_wgu), e + L.gu, nullptr, T, 2 * f, h, h, 2 * f, 2 * f));
-  LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, e + L.z, T, f, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->off_wd), out, e + L.h, T, h, f, f, h, h));
+  const int64_t lh = s->ld_h, lq = s->ld_qkv, lo = s->ld_qd, lg = s->ld_gu, lf = s->ld_f;
+  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.x, lh, s->param(layer, s->ioff_g1), e + L.a, lh, (float*)(e + L.r1), T, h,
+                                    c.rms_eps, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->ioff_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, lh, lq, lq));
+  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
+                                     c.head_dim, lq, 1.f, s->st));
+  LAUNCH(CLS_ATTN_FWD, mls::attn_fwd(s->dt, e + L.qkv, lq, e + L.o, lo, (float*)(e + L.lse), c.micro_batch, c.seq,
+                                     c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->ioff_wo), e + L.h, e + L.x, T, h, s->qd, lo, lh, lh, lh));
+  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.h, lh, s->param(layer, s->ioff_g2), e + L.b, lh, (float*)(e + L.r2), T, h,
+                                    c.rms_eps, s->st));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->ioff_wgu), e + L.gu, nullptr, T, 2 * f, h, lh, lg, lg));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, lg, e + L.z, lf, T, f, s->st));
+  // `out` is either the next layer's x (row stride ld_h) or the caller's dense y
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->ioff_wd), out, e + L.h, T, h, f, lf, lh, ld_out, lh));
   return MLS_OK;
 }
 
-// ---- one decoder layer, backward.  dy: gradient w.r.t. the layer output; dx receives the gradient w.r.t. its
-// input; g: this layer's slice of the caller's fp32 gradient vector (accumulated into).
-int layer_backward(mls_stage* s, int layer, const char* e, const void* dy, void* dx, float* g) {
+// ---- one decoder layer, backward.  dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the
+// gradient w.r.t. its input (row stride ld_dx); g: this layer's slice of the caller's fp32 gradient vector.
+int layer_backward(mls_stage* s, int layer, const char* e, const void* dy, int64_t ld_dy, void* dx, int64_t ld_dx,
+                   float* g) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, w = s->qkvw;
+  const int64_t lh = s->ld_h, lq = s->ld_qkv, lo = s->ld_qd, lg = s->ld_gu, lf = s->ld_f;
   // MLP
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->off_wd), s->dz, nullptr, T, f, h, h, h, f));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, f, h, h));
-  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, e + L.gu, s->dgu, T, f, s->st));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->off_wgu), s->dbuf, nullptr, T, h, 2 * f, 2 * f, 2 * f, h));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, h, 2 * f, 2 * f));
-  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.h, s->param(layer, s->off_g2), (const float*)(e + L.r2), dy, s->dh,
-                           g + s->off_g2, s->partial, T, h, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->ioff_wd), s->dz, nullptr, T, f, h, ld_dy, lh, lf));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, lf, ld_dy, h));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, s->dgu, lg, T, f, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, lh, lg, 2 * f));
+  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
+                                    dy, ld_dy, s->dh, lh, g + s->off_g2, s->partial, T, h, s->st));
   // attention
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->off_wo), s->dc, nullptr, T, qd, h, h, h, qd));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, qd, h, h));
-  LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, e + L.o, (const float*)(e + L.lse), s->dc, s->dqkv, s->delta, c.micro_batch,
-                        c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
-  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, w,
-                            -1.f, s->st));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->off_wqkv), s->dbuf, nullptr, T, h, w, w, w, h));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, h, w, w));
-  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, e + L.x, s->param(layer, s->off_g1), (const float*)(e + L.r1), s->dh, dx,
-                           g + s->off_g1, s->partial, T, h, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, lo, lh, h));
+  LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, s->dqkv, lq,
+                                     s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
+  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
+                                     c.head_dim, lq, -1.f, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, w, lq, lq, lh));
+  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, lh, lq, w));
+  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
+                                    s->dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st));
   return MLS_OK;
 }
 
@@ -238,18 +266,30 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   s->off_wgu = s->off_g2 + h;
   s->off_wd = s->off_wgu + h * 2 * f;
   s->layer_params = s->off_wd + f * h;
+  s->ld_h = padded(c.hidden);
+  s->ld_qkv = padded(s->qkvw);
+  s->ld_qd = padded(s->qd);
+  s->ld_gu = padded(2 * int64_t(c.ffn));
+  s->ld_f = padded(c.ffn);
+  s->ioff_g1 = 0;
+  s->ioff_wqkv = h;
+  s->ioff_wo = s->ioff_wqkv + h * s->ld_qkv;
+  s->ioff_g2 = s->ioff_wo + size_t(s->qd) * s->ld_h;
+  s->ioff_wgu = s->ioff_g2 + h;
+  s->ioff_wd = s->ioff_wgu + h * s->ld_gu;
+  s->ilayer_params = s->ioff_wd + f * s->ld_h;
 
   LayerStash& L = s->ls;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
-  L.x = take(T * h * s->es);
-  L.a = take(T * h * s->es);
-  L.qkv = take(T * s->qkvw * s->es);
-  L.o = take(T * s->qd * s->es);
-  L.h = take(T * h * s->es);
-  L.b = take(T * h * s->es);
-  L.gu = take(T * 2 * f * s->es);
-  L.z = take(T * f * s->es);
+  L.x = take(T * s->ld_h * s->es);
+  L.a = take(T * s->ld_h * s->es);
+  L.qkv = take(T * s->ld_qkv * s->es);
+  L.o = take(T * s->ld_qd * s->es);
+  L.h = take(T * s->ld_h * s->es);
+  L.b = take(T * s->ld_h * s->es);
+  L.gu = take(T * s->ld_gu * s->es);
+  L.z = take(T * s->ld_f * s->es);
   L.r1 = take(T * 4);
   L.r2 = take(T * 4);
   L.lse = take(size_t(c.micro_batch) * c.n_q_heads * c.seq * 4);
@@ -259,18 +299,18 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   auto alloc = [&](void** p, size_t bytes) { return hipMalloc(p, bytes ? bytes : 256); };
   hipError_t e = hipSuccess;
   const int nb = mls::rmsnorm_bwd_blocks(s->T);
-  if ((e = alloc((void**)&s->params, size_t(c.max_layers) * s->layer_params * s->es)) != hipSuccess ||
+  if ((e = alloc((void**)&s->params, size_t(c.max_layers) * s->ilayer_params * s->es)) != hipSuccess ||
       (e = alloc((void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
       (e = alloc((void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
       (e = alloc((void**)&s->stash, size_t(c.max_inflight) * c.max_layers * L.bytes)) != hipSuccess ||
-      (e = alloc((void**)&s->g0, T * h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->g1, T * h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dz, T * f * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dgu, T * 2 * f * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dbuf, T * h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dh, T * h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dc, T * s->qd * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dqkv, T * s->qkvw * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->g0, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->g1, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dz, T * s->ld_f * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dgu, T * s->ld_gu * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dbuf, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dh, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dc, T * s->ld_qd * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dqkv, T * s->ld_qkv * s->es)) != hipSuccess ||
       (e = alloc((void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4)) != hipSuccess ||
       (e = alloc((void**)&s->partial, size_t(nb) * h * 4)) != hipSuccess) {
     release(s);
@@ -315,10 +355,11 @@ int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y) {
   if (k_layers == 0) {
     HIP_TRY(hipMemcpyAsync(y, x, act, hipMemcpyDeviceToDevice, s->st));
   } else {
-    HIP_TRY(hipMemcpyAsync(s->slot_layer(slot, 0) + s->ls.x, x, act, hipMemcpyDeviceToDevice, s->st));
+    HIP_TRY(copy2d(s, s->slot_layer(slot, 0) + s->ls.x, s->ld_h, x, s->c.hidden, s->T, s->c.hidden));
     for (int l = 0; l < k_layers; l++) {
-      void* out = l + 1 < k_layers ? (void*)(s->slot_layer(slot, l + 1) + s->ls.x) : y;
-      if (int rc = layer_forward(s, l, s->slot_layer(slot, l), out)) return rc;
+      const bool last = l + 1 == k_layers;
+      void* out = last ? y : (void*)(s->slot_layer(slot, l + 1) + s->ls.x);
+      if (int rc = layer_forward(s, l, s->slot_layer(slot, l), out, last ? s->c.hidden : s->ld_h)) return rc;
     }
   }
   s->slot_k[slot] = k_layers;
@@ -342,11 +383,16 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
       if (dx != dy) HIP_TRY(hipMemcpyAsync(dx, dy, act, hipMemcpyDeviceToDevice, s->st));
     } else {
       const void* cur = dy;
+      int64_t ld_cur = s->c.hidden;  // the caller's buffers are dense, the ping-pong buffers row-padded
       for (int l = k - 1; l >= 0; l--) {
         void* out = l == 0 ? (void*)dx : (void*)((l & 1) ? s->g1 : s->g0);
+        const int64_t ld_out = l == 0 ? s->c.hidden : s->ld_h;
         s->last_dy = cur;
-        if (int rc = layer_backward(s, l, s->slot_layer(slot, l), cur, out, grads + size_t(l) * s->layer_params)) return rc;
+        s->last_dy_ld = ld_cur;
+        if (int rc = layer_backward(s, l, s->slot_layer(slot, l), cur, ld_cur, out, ld_out, grads + size_t(l) * s->layer_params))
+          return rc;
         cur = out;
+        ld_cur = ld_out;
       }
     }
     s->head = (s->head + 1) % s->c.max_inflight;
@@ -385,14 +431,24 @@ int mls_stage_param_layout(const mls_stage* s, int32_t layer, int32_t which, siz
 
 int mls_stage_get_params(mls_stage* s, void* dst) {
   if (!s || !dst) return fail(MLS_E_NULL, "mls_stage_get_params: null argument");
-  HIP_TRY(hipMemcpyAsync(dst, s->params, mls_stage_grad_elems(s) * s->es, hipMemcpyDeviceToDevice, s->st));
+  PTensor t[6];
+  param_tensors(s, t);
+  for (int l = 0; l < s->c.max_layers; l++)
+    for (auto& e : t)
+      HIP_TRY(copy2d(s, (char*)dst + (size_t(l) * s->layer_params + e.off) * s->es, e.cols, s->param(l, e.ioff), e.ld,
+                     e.rows, e.cols));
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
 
 int mls_stage_set_params(mls_stage* s, const void* src) {
   if (!s || !src) return fail(MLS_E_NULL, "mls_stage_set_params: null argument");
-  HIP_TRY(hipMemcpyAsync(s->params, src, mls_stage_grad_elems(s) * s->es, hipMemcpyDeviceToDevice, s->st));
+  PTensor t[6];
+  param_tensors(s, t);
+  for (int l = 0; l < s->c.max_layers; l++)
+    for (auto& e : t)
+      HIP_TRY(copy2d(s, s->param(l, e.ioff), e.ld, (const char*)src + (size_t(l) * s->layer_params + e.off) * s->es,
+                     e.cols, e.rows, e.cols));
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
@@ -408,18 +464,18 @@ int mls_stage_reset(mls_stage* s) {
 
 int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, void* dst) {
   if (!s || !dst) return fail(MLS_E_NULL, "mls_stage_debug_read: null argument");
-  const size_t T = s->T, h = s->c.hidden, f = s->c.ffn, es = s->es;
+  const int64_t T = s->T, h = s->c.hidden, f = s->c.ffn;
   const void* src = nullptr;
-  size_t bytes = 0;
+  int64_t cols = 0, ld = 0;
   if (id >= MLS_T_DY) {
     switch (id) {
-      case MLS_T_DY: src = s->last_dy; bytes = T * h * es; break;
-      case MLS_T_DGU: src = s->dgu; bytes = T * 2 * f * es; break;
-      case MLS_T_DH: src = s->dh; bytes = T * h * es; break;
-      case MLS_T_DQKV: src = s->dqkv; bytes = T * s->qkvw * es; break;
+      case MLS_T_DY: src = s->last_dy; cols = h; ld = s->last_dy_ld; break;
+      case MLS_T_DGU: src = s->dgu; cols = 2 * f; ld = s->ld_gu; break;
+      case MLS_T_DH: src = s->dh; cols = h; ld = s->ld_h; break;
+      case MLS_T_DQKV: src = s->dqkv; cols = s->qkvw; ld = s->ld_qkv; break;
       default: return fail(MLS_E_RANGE, "unknown tensor id");
     }
-    if (!src) return fail(MLS_E_RANGE, "no backward has run yet");
+    if (!s->last_dy) return fail(MLS_E_RANGE, "no backward has run yet");
   } else {
     if (slot < 0 || slot >= s->count) return fail(MLS_E_RANGE, "stash slot out of range");
     const int phys = (s->head + slot) % s->c.max_inflight;
@@ -427,19 +483,23 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
     const char* e = s->slot_layer(phys, layer);
     const LayerStash& L = s->ls;
     switch (id) {
-      case MLS_T_X: src = e + L.x; bytes = T * h * es; break;
-      case MLS_T_A: src = e + L.a; bytes = T * h * es; break;
-      case MLS_T_QKV: src = e + L.qkv; bytes = T * s->qkvw * es; break;
-      case MLS_T_O: src = e + L.o; bytes = T * s->qd * es; break;
-      case MLS_T_H: src = e + L.h; bytes = T * h * es; break;
-      case MLS_T_B: src = e + L.b; bytes = T * h * es; break;
-      case MLS_T_GU: src = e + L.gu; bytes = T * 2 * f * es; break;
-      case MLS_T_Z: src = e + L.z; bytes = T * f * es; break;
-      case MLS_T_LSE: src = e + L.lse; bytes = size_t(s->c.micro_batch) * s->c.n_q_heads * s->c.seq * 4; break;
+      case MLS_T_X: src = e + L.x; cols = h; ld = s->ld_h; break;
+      case MLS_T_A: src = e + L.a; cols = h; ld = s->ld_h; break;
+      case MLS_T_QKV: src = e + L.qkv; cols = s->qkvw; ld = s->ld_qkv; break;
+      case MLS_T_O: src = e + L.o; cols = s->qd; ld = s->ld_qd; break;
+      case MLS_T_H: src = e + L.h; cols = h; ld = s->ld_h; break;
+      case MLS_T_B: src = e + L.b; cols = h; ld = s->ld_h; break;
+      case MLS_T_GU: src = e + L.gu; cols = 2 * f; ld = s->ld_gu; break;
+      case MLS_T_Z: src = e + L.z; cols = f; ld = s->ld_f; break;
+      case MLS_T_LSE:
+        HIP_TRY(hipMemcpyAsync(dst, e + L.lse, size_t(s->c.micro_batch) * s->c.n_q_heads * s->c.seq * 4,
+                               hipMemcpyDeviceToDevice, s->st));
+        HIP_TRY(hipStreamSynchronize(s->st));
+        return MLS_OK;
       default: return fail(MLS_E_RANGE, "unknown tensor id");
     }
   }
-  HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s->st));
+  HIP_TRY(copy2d(s, dst, cols, src, ld, T, cols));  // dst is dense
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
@@ -482,8 +542,8 @@ int mls_gemm(int32_t dtype, int32_t mode, const void* A, int64_t lda, const void
   if (lda < a_len || ldb < b_len || ldc < N || lda % 8 || ldb % 8 || ldc % 8)
     return fail(MLS_E_CONFIG, "mls_gemm: a row stride must be a multiple of 8 not below the row length");
   hipStream_t st = (hipStream_t)hip_stream;
-  hipError_t e = dtype == MLS_BF16 ? mls::gemm_bf16(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, st)
-                                   : mls::gemm_f32(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, st);
+  hipError_t e = dtype == MLS_BF16 ? mls::gemm_bf16(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, ldc, st)
+                                   : mls::gemm_f32(mode, A, B, C, R, (int)M, (int)N, (int)K, lda, ldb, ldc, ldc, st);
   if (e != hipSuccess) return fail_hip(e, "mls_gemm launch");
   return MLS_OK;
 }
