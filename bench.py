@@ -48,16 +48,76 @@ def cpu_baseline(sh):
             "tokens_per_s": one.tokens / dt}
 
 
+def plan_sweep(a):
+    print(json.dumps(run_plan_sweep(None, a.steps)))
+
+
+def run_plan_sweep(plans, steps):
+    """The straggler-shaped plan sweep: 16 seeded (layers, micro-batches) plans on the 7B layer shape at seq 2048;
+    checks the paper's cost model (Sec. 4.2: stage time = l * tau(b) per micro-batch, step ~ m * l * tau(b)) by a
+    least-squares fit t = alpha + c * l * m and reports the largest relative residual."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2410_13333_amd as mls
+    from tests.helpers import to_device
+    sh = synth.CONFIGS["sweep"]
+    plans = plans or synth.plan_sweep()
+    sh = sh.with_(layers=max(k for k, _ in plans), microbatches=max(m for _, m in plans))
+    st = mls.Stage.from_shape(sh, seed=1004)           # one handle serves every plan
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    mmax = max(m for _, m in plans)
+    xs = [to_device(synth.make_x(sh, 2004, mb)[0], sh.dtype) for mb in range(mmax)]
+    dy = torch.stack([to_device(synth.make_dy(sh, 3004, mb)[0], sh.dtype) for mb in range(mmax)])
+    ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(mmax)]
+    dx = torch.empty_like(dy)
+    grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+    times = []
+    for k, m in plans:
+        def step():
+            grads.zero_()
+            for mb in range(m):
+                st.forward(xs[mb], k, ys[mb])
+            st.backward(dy[:m], grads, m, dx[:m])
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3 / steps)
+    km = np.array([k * m for k, m in plans], dtype=np.float64)
+    t = np.array(times)
+    A = np.stack([np.ones_like(km), km], axis=1)
+    (alpha, c), *_ = np.linalg.lstsq(A, t, rcond=None)
+    fit = alpha + c * km
+    resid = np.abs(t - fit) / t
+    flops_unit = sh.model_flops_layer_mb()
+    out = {"metric": "stage fwd+bwd TFLOP/s (bf16)", "value": flops_unit / (c * 1e-3) / 1e12, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": steps, "warmup": 1, "ms_per_step": float(t.mean()), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "plan sweep: 7B layer shape, seq 2048, 16 seeded plans (layers 2..9, micro-batches 1..16)"},
+           "tau_ms_per_layer_microbatch": float(c), "alpha_ms": float(alpha),
+           "max_relative_residual": float(resid.max()),
+           "r2": float(1 - np.sum((t - fit) ** 2) / np.sum((t - t.mean()) ** 2)),
+           "plans": [{"layers": k, "microbatches": m, "ms": float(ms)} for (k, m), ms in zip(plans, times)]}
+    st.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny")
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    if a.workload == "sweep":
+        return plan_sweep(a)
 
     import torch
     import synth

@@ -407,39 +407,40 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
     if (i0 + TR - 1 >= jw) {  // wave-uniform: some query row at or below this wave's first key row
       const bf16_t* qs = lds[cur][0];
       const bf16_t* ds_ = lds[cur][1];
-      f32x16 st[2], dp[2];
+      const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
 #pragma unroll
-      for (int itl = 0; itl < 2; itl++) {
-        st[itl] = zero16();
-        dp[itl] = zero16();
+      for (int itl = 0; itl < 2; itl++) {  // one 32-row query tile at a time keeps the live registers down
+        f32x16 st = zero16(), dp = zero16();
 #pragma unroll
         for (int kk = 0; kk < KD; kk++) {
-          st[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st[itl], 0, 0, 0);
-          dp[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp[itl], 0, 0, 0);
-        }
-      }
-      const bool diag = i0 < jw + 31;
-#pragma unroll
-      for (int itl = 0; itl < 2; itl++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-          float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
-          if ((diag && i0 + r < ji) || i0 + r >= S) p = 0.f;
-          st[itl][e] = p;
-          dp[itl][e] = p * (dp[itl][e] - stat[cur][1][r]);
+          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp, 0, 0, 0);
         }
 #pragma unroll
-      for (int itl = 0; itl < 2; itl++)
+        for (int g = 0; g < 4; g++) {
+          const int r0 = itl * 32 + (lane >> 5) * 4 + 8 * g;
+          const float4 l4 = *reinterpret_cast<const float4*>(&stat[cur][0][r0]);
+          const float4 d4 = *reinterpret_cast<const float4*>(&stat[cur][1][r0]);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int s = 0; s < 2; s++) {
-          const bf16x8 pf = acc_to_b(st[itl], s), df = acc_to_b(dp[itl], s);
-#pragma unroll
-          for (int t = 0; t < DT; t++) {
-            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ds_, t, itl * 2 + s, lane), pf, dv[t], 0, 0, 0);
-            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(qs, t, itl * 2 + s, lane), df, dk[t], 0, 0, 0);
+          for (int rr = 0; rr < 4; rr++) {
+            const int e = g * 4 + rr;
+            float p = __builtin_amdgcn_exp2f(st[e] * sc - lv[rr]);
+            if (diag && (i0 + r0 + rr < ji || i0 + r0 + rr >= S)) p = 0.f;
+            st[e] = p;
+            dp[e] = p * (dp[e] - dv4[rr]);
           }
         }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; s2++) {
+          const bf16x8 pf = acc_to_b(st, s2), df = acc_to_b(dp, s2);
+#pragma unroll
+          for (int t = 0; t < DT; t++) {
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ds_, t, itl * 2 + s2, lane), pf, dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(qs, t, itl * 2 + s2, lane), df, dk[t], 0, 0, 0);
+          }
+        }
+      }
     }
     if (it + 1 < niter) put_stat(it + 1);
   }

@@ -1,0 +1,19 @@
+"""The paper's cost-model claim on one GPU: stage step time is linear in layers x micro-batches (Sec. 4.2,
+t = y * l * tau(b), step ~ m * max t; the paper reports a cost-model error of at most 6.3 %).  Six of the
+sixteen seeded plans at the real layer shape; the least-squares line must fit within 5 %."""
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.timeout(300)
+def test_stage_time_is_linear_in_layers_times_microbatches():
+    import bench
+    plans = [p for p in synth.plan_sweep() if p[0] * p[1] <= 40][:6]
+    assert len(plans) >= 5 and len({k * m for k, m in plans}) >= 4
+    out = bench.run_plan_sweep(plans, steps=2)
+    print(out["tau_ms_per_layer_microbatch"], out["alpha_ms"], out["max_relative_residual"])
+    assert out["max_relative_residual"] <= 0.05
+    assert out["r2"] >= 0.999
