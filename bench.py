@@ -161,11 +161,13 @@ def main():
 
     flops_step = sh.model_flops_layer_mb() * K * M
     tflops = flops_step / (ms * 1e-3) / 1e12
-    # dominant kernel: the bf16 MFMA GEMM (12 launches per layer per micro-batch)
+    # dominant kernel: the bf16 MFMA GEMM (per layer: 8 launches per micro-batch + 4 weight-gradient launches)
     gemm_ms = sum(tm[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
     gemm_n = sum(tm[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
-    gemm_flops_launch = 3 * 2 * sh.tokens * sh.matrix_params() / 12.0
-    achieved = gemm_flops_launch / (gemm_ms / gemm_n * 1e-3) / 1e12
+    # algorithmic FLOPs of all GEMM launches of the timed steps / their summed duration; per launch = / launches
+    gemm_flops = 3 * 2 * sh.tokens * sh.matrix_params() * K * M * a.steps
+    gemm_flops_launch = gemm_flops / gemm_n
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
     out = {
         "metric": "stage fwd+bwd TFLOP/s (bf16)", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -69,8 +69,8 @@ enum {
   MLS_T_GU = 6,   /* gate|up                  [T, 2*ffn]                                    */
   MLS_T_Z = 7,    /* SwiGLU output            [T, ffn]                                      */
   MLS_T_LSE = 8,  /* natural-log softmax denominators, fp32 [micro_batch, n_q_heads, seq]   */
-  /* the upstream-gradient operands of the LAST layer processed by the most recent backward call
-     (workspace, overwritten by every layer): */
+  /* the upstream-gradient operands of the LAST (layer, micro-batch) pair processed by the most recent backward
+     call, i.e. layer 0 of its last micro-batch (workspace, overwritten by later calls): */
   MLS_T_DY = 16,   /* gradient w.r.t. the layer output   [T, hidden]                        */
   MLS_T_DGU = 17,  /* gradient w.r.t. gate|up            [T, 2*ffn]                         */
   MLS_T_DH = 18,   /* gradient w.r.t. h                  [T, hidden]                        */
@@ -111,8 +111,9 @@ int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y);
 /* Backward over the n_microbatches oldest stash entries, in push order (the m_i of Eq. 1).
  * dY, dX: [n, b, S, hidden] in the storage type (entry i uses slice i); dX may alias dY.
  * grads: fp32, public layout, mls_stage_grad_elems() floats; the library only ever adds to it
- * (G += sum over the micro-batches, ascending order), it never zeroes it.  Entries forwarded with
- * different k_layers may be mixed.  n = 0 is a no-op.  Errors: MLS_E_NULL, MLS_E_RANGE (n < 0),
+ * (G += sum over the micro-batches: per layer the contributions of all n micro-batches are contracted in one
+ * pass, in ascending order, and added to G once), it never zeroes it.  Entries forwarded with different k_layers
+ * may be mixed.  n = 0 is a no-op.  Errors: MLS_E_NULL, MLS_E_RANGE (n < 0),
  * MLS_E_STASH (n exceeds the stashed entries), MLS_E_HIP. */
 int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n_microbatches, void* dX);
 

@@ -42,6 +42,15 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
 
 constexpr uint32_t OOB = 0x80000000u;  // beyond any num_records accepted by the launcher
 
+// Segmented contraction (weight gradients over several micro-batches in one launch): the contraction index runs
+// over nseg pieces of kseg rows each; piece i has its own operand base pointers, all pieces share the strides.
+constexpr int MAX_SEGS = 16;
+struct SegArgs {
+  const bf16_t* a[MAX_SEGS];
+  const bf16_t* b[MAX_SEGS];
+  int nseg, kseg;
+};
+
 // ---- [row][k] tile: ROWS x BK elements, BK*2 bytes per row
 template <int ROWS, int BK>
 struct RowTile {
@@ -106,11 +115,12 @@ struct ColTile {
   }
 };
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW, bool SEG>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                        void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-                                                       int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m) {
+                                                       int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m,
+                                                       SegArgs segs) {
   using AT_R = RowTile<BM, BK>;
   using AT_C = ColTile<BM, BK>;
   using BT_R = RowTile<BN, BK>;
@@ -133,7 +143,20 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
 
-  const i32x4 ra = make_rsrc(A, a_bytes), rb = make_rsrc(B, b_bytes);
+  // prefetch cursor: the k-tile the next DMA instructions fetch (piece pf_seg, first row pf_k0)
+  i32x4 ra = make_rsrc(SEG ? segs.a[0] : A, a_bytes), rb = make_rsrc(SEG ? segs.b[0] : B, b_bytes);
+  int pf_seg = 0, pf_k0 = 0;
+  const int kpiece = SEG ? segs.kseg : K;
+  auto advance = [&]() {
+    pf_k0 += BK;
+    if (SEG && pf_k0 >= kpiece) {
+      pf_k0 = 0;
+      pf_seg++;
+      const int i = pf_seg < segs.nseg ? pf_seg : segs.nseg - 1;
+      ra = make_rsrc(segs.a[i], a_bytes);
+      rb = make_rsrc(segs.b[i], b_bytes);
+    }
+  };
   AT_R atr;
   AT_C atc;
   BT_R btr;
@@ -146,13 +169,13 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   // DMA instruction d (0 .. LPT-1) of this wave for k-tile kt into `stage`: the first NIA belong to A
   // (`live` false: the tile does not exist; the load is sent out of range and only zero-fills a dead stage, which
   // keeps the number of loads per k-step, and with it the vmcnt bookkeeping, constant and the loop branch-free)
-  auto fire = [&](int d, int kt, int stage, bool live) {
-    const int k0 = kt * BK;
+  auto fire = [&](int d, int stage, bool live) {
+    const int k0 = pf_k0;
     if (d < NIA) {
-      const uint32_t v = ATR ? atc.voff(d, k0, K, lda) : atr.voff(d, k0, K, lda);
+      const uint32_t v = ATR ? atc.voff(d, k0, kpiece, lda) : atr.voff(d, k0, kpiece, lda);
       dma16(ra, live ? v : OOB, a_wave + stage * STAGE + d * 1024);
     } else {
-      const uint32_t v = BTR ? btc.voff(d - NIA, k0, K, ldb) : btr.voff(d - NIA, k0, K, ldb);
+      const uint32_t v = BTR ? btc.voff(d - NIA, k0, kpiece, ldb) : btr.voff(d - NIA, k0, kpiece, ldb);
       dma16(rb, live ? v : OOB, b_wave + stage * STAGE + (d - NIA) * 1024);
     }
   };
@@ -165,11 +188,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  const int nk = (K + BK - 1) / BK;
+  const int nk = (SEG ? segs.nseg : 1) * ((kpiece + BK - 1) / BK);
 #pragma unroll
   for (int s = 0; s < NS - 1; s++) {
 #pragma unroll
-    for (int d = 0; d < LPT; d++) fire(d, s, s, s < nk);
+    for (int d = 0; d < LPT; d++) fire(d, s, s < nk);
+    advance();
   }
 
   // LDS reads per 16-wide k-substep and the MFMA : read interleave the scheduler is asked for
@@ -187,12 +211,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   };
   // one 16-wide k-substep: fire this substep's share of the next tile's DMA between the two halves of the MFMA
   // block (operands swapped: the lane ends up with 4 consecutive columns of one row)
-  auto mfma_block = [&](int kk, int kt, int pstage, bool prefetch) {
+  auto mfma_block = [&](int kk, int pstage, bool prefetch) {
 #pragma unroll
     for (int i = 0; i < TM; i++) {
       if (i == TM / 2) {
 #pragma unroll
-        for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, kt + NS - 1, pstage, prefetch);
+        for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, pstage, prefetch);
       }
 #pragma unroll
       for (int j = 0; j < TN; j++)
@@ -227,9 +251,10 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int kk = 0; kk < KS; kk++) {
         __builtin_amdgcn_sched_barrier(0);
         if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1); else lfrag(smem + nstage * STAGE, 0, 0);
-        mfma_block(kk, kt, pstage, prefetch);
+        mfma_block(kk, pstage, prefetch);
         interleave_hint();
       }
+      advance();
       stage = nstage;
     }
   } else {
@@ -245,9 +270,10 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int kk = 0; kk < KS; kk++) {
         __builtin_amdgcn_sched_barrier(0);
         if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1);
-        mfma_block(kk, kt, pstage, prefetch);
+        mfma_block(kk, pstage, prefetch);
         if (kk + 1 < KS) interleave_hint();
       }
+      advance();
       stage = stage + 1 == NS ? 0 : stage + 1;
     }
   }
@@ -288,11 +314,14 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   }
 }
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW = false>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW = false, bool SEG = false>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                  int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
+                  int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
+                  const SegArgs* segs = nullptr) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
-  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, SKEW>;
+  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, SKEW, SEG>;
+  SegArgs sa = {};
+  if (segs) sa = *segs;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -300,7 +329,7 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
     attr_set = true;
   }
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm);
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm, sa);
   return hipGetLastError();
 }
 
@@ -341,6 +370,30 @@ hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const 
     case GEMM_TN: return dispatch<true, true, EPI_F32_ACC>(a, b, C, r, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
   }
   return hipErrorInvalidValue;
+}
+
+bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb) { return gemm_bf16_dma_ok(GEMM_TN, 8, 8, kseg, lda, ldb); }
+
+// C[M,N] += sum_i A_i[kseg,M]^T * B_i[kseg,N] (fp32 C), the contraction of all pieces accumulated in registers and
+// added to C once: the weight gradient of several micro-batches in one launch.  nseg <= 16.
+hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st) {
+  if (M == 0 || N == 0 || nseg == 0 || kseg == 0) return hipSuccess;
+  if (nseg > MAX_SEGS) return hipErrorInvalidValue;
+  SegArgs sa = {};
+  for (int i = 0; i < nseg; i++) {
+    sa.a[i] = static_cast<const bf16_t*>(A[i]);
+    sa.b[i] = static_cast<const bf16_t*>(B[i]);
+  }
+  sa.nseg = nseg;
+  sa.kseg = kseg;
+  const uint32_t ab = uint32_t(int64_t(kseg) * lda * 2), bb = uint32_t(int64_t(kseg) * ldb * 2);
+  const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
+  if (big_tiles >= 192)
+    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
+                                                                      ldc, 0, ab, bb, st, &sa);
+  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, false, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
+                                                                     ldc, 0, ab, bb, st, &sa);
 }
 
 }  // namespace mls

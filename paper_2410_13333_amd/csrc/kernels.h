@@ -18,6 +18,11 @@ hipError_t gemm_bf16(int mode, const void* A, const void* B, void* C, const void
 bool gemm_bf16_dma_ok(int mode, int M, int N, int K, int64_t lda, int64_t ldb);
 hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K,
                          int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st);
+// weight gradient of several micro-batches in one launch: C[M,N] += sum_i A_i[kseg,M]^T * B_i[kseg,N], C fp32,
+// at most 16 pieces, all with the same strides; true if the operands fit the DMA path's 31-bit offsets
+bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb);
+hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st);
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st);
 

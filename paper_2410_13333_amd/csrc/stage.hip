@@ -90,12 +90,16 @@ struct mls_stage {
   char* stash = nullptr;  // [max_inflight][max_layers] LayerStash
   std::vector<int> slot_k;
   int head = 0, count = 0;  // FIFO ring over the slots
-  // backward workspace
+  // backward workspace.  g0, g1 (ping-pong gradient of the residual stream), dgu, dh and dqkv exist once per
+  // in-flight micro-batch (they are the operands of the weight-gradient contractions, which run once per layer
+  // over all micro-batches of a backward call); dz, dbuf and dc are transient and shared.
   char *g0 = nullptr, *g1 = nullptr, *dz = nullptr, *dgu = nullptr, *dbuf = nullptr, *dh = nullptr, *dc = nullptr,
        *dqkv = nullptr;
+  size_t mb_h = 0, mb_gu = 0, mb_qkv = 0;  // bytes per micro-batch of the [T,ld_h], [T,ld_gu], [T,ld_qkv] buffers
   float *delta = nullptr, *partial = nullptr;
   const void* last_dy = nullptr;
   int64_t last_dy_ld = 0;
+  int last_ws = 0;  // micro-batch workspace used by the most recent layer backward
   Timing tm;
 
   char* slot_layer(int slot, int layer) const {
@@ -198,33 +202,47 @@ int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
   return MLS_OK;
 }
 
-// ---- one decoder layer, backward.  dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the
-// gradient w.r.t. its input (row stride ld_dx); g: this layer's slice of the caller's fp32 gradient vector.
-int layer_backward(mls_stage* s, int layer, const char* e, const void* dy, int64_t ld_dy, void* dx, int64_t ld_dx,
-                   float* g) {
+// ---- one decoder layer, backward, for micro-batch workspace `w`: everything except the four weight-gradient
+// contractions, whose operands (dy, dgu, dh, dqkv of this micro-batch) stay in the workspace for them.
+// dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the gradient w.r.t. its input (row stride
+// ld_dx); g: this layer's slice of the caller's fp32 gradient vector (gains only here).
+int layer_backward_data(mls_stage* s, int layer, const char* e, int w, const void* dy, int64_t ld_dy, void* dx,
+                        int64_t ld_dx, float* g) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
-  const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, w = s->qkvw;
+  const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, wq = s->qkvw;
   const int64_t lh = s->ld_h, lq = s->ld_qkv, lo = s->ld_qd, lg = s->ld_gu, lf = s->ld_f;
+  char* dgu = s->dgu + size_t(w) * s->mb_gu;
+  char* dh = s->dh + size_t(w) * s->mb_h;
+  char* dqkv = s->dqkv + size_t(w) * s->mb_qkv;
   // MLP
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->ioff_wd), s->dz, nullptr, T, f, h, ld_dy, lh, lf));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.z, dy, g + s->off_wd, nullptr, f, h, T, lf, ld_dy, h));
-  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, s->dgu, lg, T, f, s->st));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.b, s->dgu, g + s->off_wgu, nullptr, h, 2 * f, T, lh, lg, 2 * f));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
-                                    dy, ld_dy, s->dh, lh, g + s->off_g2, s->partial, T, h, s->st));
+                                    dy, ld_dy, dh, lh, g + s->off_g2, s->partial, T, h, s->st));
   // attention
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.o, s->dh, g + s->off_wo, nullptr, qd, h, T, lo, lh, h));
-  LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, s->dqkv, lq,
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
+  LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
                                      s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
-  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, s->dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
+  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
                                      c.head_dim, lq, -1.f, s->st));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, s->dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, w, lq, lq, lh));
-  LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, e + L.a, s->dqkv, g + s->off_wqkv, nullptr, h, w, T, lh, lq, w));
+  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
-                                    s->dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st));
+                                    dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st));
+  return MLS_OK;
+}
+
+// C[M,N] += sum_i A_i[T,M]^T B_i[T,N] over n micro-batches (fp32 C): one launch per 16 micro-batches on the bf16
+// DMA path, one launch per micro-batch otherwise
+int wgrad(mls_stage* s, const void* const* A, const void* const* B, int n, float* C, int M, int N, int64_t lda,
+          int64_t ldb) {
+  if (s->dt == mls::DT_BF16 && mls::gemm_tn_segments_ok(s->T, lda, ldb)) {
+    for (int i = 0; i < n; i += 16)
+      LAUNCH(CLS_GEMM_TN, mls::gemm_bf16_tn_segments(A + i, B + i, n - i < 16 ? n - i : 16, C, M, N, s->T, lda, ldb, N, s->st));
+  } else {
+    for (int i = 0; i < n; i++) LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, A[i], B[i], C, nullptr, M, N, s->T, lda, ldb, N));
+  }
   return MLS_OK;
 }
 
@@ -297,20 +315,24 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   s->slot_k.assign(c.max_inflight, 0);
 
   auto alloc = [&](void** p, size_t bytes) { return hipMalloc(p, bytes ? bytes : 256); };
+  const size_t nmb = c.max_inflight;
+  s->mb_h = align256(T * s->ld_h * s->es);
+  s->mb_gu = align256(T * s->ld_gu * s->es);
+  s->mb_qkv = align256(T * s->ld_qkv * s->es);
   hipError_t e = hipSuccess;
   const int nb = mls::rmsnorm_bwd_blocks(s->T);
   if ((e = alloc((void**)&s->params, size_t(c.max_layers) * s->ilayer_params * s->es)) != hipSuccess ||
       (e = alloc((void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
       (e = alloc((void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
       (e = alloc((void**)&s->stash, size_t(c.max_inflight) * c.max_layers * L.bytes)) != hipSuccess ||
-      (e = alloc((void**)&s->g0, T * s->ld_h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->g1, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->g0, nmb * s->mb_h)) != hipSuccess ||
+      (e = alloc((void**)&s->g1, nmb * s->mb_h)) != hipSuccess ||
       (e = alloc((void**)&s->dz, T * s->ld_f * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dgu, T * s->ld_gu * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dgu, nmb * s->mb_gu)) != hipSuccess ||
       (e = alloc((void**)&s->dbuf, T * s->ld_h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dh, T * s->ld_h * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dh, nmb * s->mb_h)) != hipSuccess ||
       (e = alloc((void**)&s->dc, T * s->ld_qd * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dqkv, T * s->ld_qkv * s->es)) != hipSuccess ||
+      (e = alloc((void**)&s->dqkv, nmb * s->mb_qkv)) != hipSuccess ||
       (e = alloc((void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4)) != hipSuccess ||
       (e = alloc((void**)&s->partial, size_t(nb) * h * 4)) != hipSuccess) {
     release(s);
@@ -373,31 +395,56 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
   if (n == 0) return MLS_OK;
   if (!dY || !dX || !grads) return fail(MLS_E_NULL, "mls_stage_backward: null argument");
   if (n > s->count) return fail(MLS_E_STASH, "n_microbatches exceeds the stashed micro-batches");
-  const size_t act = size_t(s->T) * s->c.hidden * s->es;
+  const mls_config& c = s->c;
+  const LayerStash& L = s->ls;
+  const size_t act = size_t(s->T) * c.hidden * s->es;
+  const int h = c.hidden, f = c.ffn;
+  // Layer-major order: for each layer, top down, first the data-gradient chain of every micro-batch that has this
+  // layer (entries may have been forwarded with different layer counts), then ONE weight-gradient contraction
+  // per weight over all of them, so the fp32 gradient is read and written once per layer, not once per micro-batch.
+  // The gradient w.r.t. the output of layer l of micro-batch i lives in its ping-pong buffer (l+1) & 1.
+  auto pp = [&](int i, int which) { return (which ? s->g1 : s->g0) + size_t(i) * s->mb_h; };
+  int kmax = 0;
+  std::vector<int> slot(n), k(n);
   for (int i = 0; i < n; i++) {
-    const int slot = s->head;
-    const int k = s->slot_k[slot];
+    slot[i] = (s->head + i) % c.max_inflight;
+    k[i] = s->slot_k[slot[i]];
+    kmax = k[i] > kmax ? k[i] : kmax;
     const char* dy = (const char*)dY + size_t(i) * act;
     char* dx = (char*)dX + size_t(i) * act;
-    if (k == 0) {
+    if (k[i] == 0) {
       if (dx != dy) HIP_TRY(hipMemcpyAsync(dx, dy, act, hipMemcpyDeviceToDevice, s->st));
     } else {
-      const void* cur = dy;
-      int64_t ld_cur = s->c.hidden;  // the caller's buffers are dense, the ping-pong buffers row-padded
-      for (int l = k - 1; l >= 0; l--) {
-        void* out = l == 0 ? (void*)dx : (void*)((l & 1) ? s->g1 : s->g0);
-        const int64_t ld_out = l == 0 ? s->c.hidden : s->ld_h;
-        s->last_dy = cur;
-        s->last_dy_ld = ld_cur;
-        if (int rc = layer_backward(s, l, s->slot_layer(slot, l), cur, ld_cur, out, ld_out, grads + size_t(l) * s->layer_params))
-          return rc;
-        cur = out;
-        ld_cur = ld_out;
-      }
+      HIP_TRY(copy2d(s, pp(i, k[i] & 1), s->ld_h, dy, h, s->T, h));
     }
-    s->head = (s->head + 1) % s->c.max_inflight;
-    s->count--;
   }
+  std::vector<const void*> az, ab, ao, aa, bdy, bdgu, bdh, bdqkv;
+  for (int l = kmax - 1; l >= 0; l--) {
+    float* g = grads + size_t(l) * s->layer_params;
+    az.clear(); ab.clear(); ao.clear(); aa.clear(); bdy.clear(); bdgu.clear(); bdh.clear(); bdqkv.clear();
+    for (int i = 0; i < n; i++) {
+      if (k[i] <= l) continue;
+      const char* e = s->slot_layer(slot[i], l);
+      const char* dy = pp(i, (l + 1) & 1);
+      void* dx = l == 0 ? (void*)((char*)dX + size_t(i) * act) : (void*)pp(i, l & 1);
+      s->last_dy = dy;
+      s->last_dy_ld = s->ld_h;
+      s->last_ws = i;
+      if (int rc = layer_backward_data(s, l, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g)) return rc;
+      az.push_back(e + L.z); ab.push_back(e + L.b); ao.push_back(e + L.o); aa.push_back(e + L.a);
+      bdy.push_back(dy);
+      bdgu.push_back(s->dgu + size_t(i) * s->mb_gu);
+      bdh.push_back(s->dh + size_t(i) * s->mb_h);
+      bdqkv.push_back(s->dqkv + size_t(i) * s->mb_qkv);
+    }
+    const int m = (int)az.size();
+    if (int rc = wgrad(s, az.data(), bdy.data(), m, g + s->off_wd, f, h, s->ld_f, s->ld_h)) return rc;
+    if (int rc = wgrad(s, ab.data(), bdgu.data(), m, g + s->off_wgu, h, 2 * f, s->ld_h, s->ld_gu)) return rc;
+    if (int rc = wgrad(s, ao.data(), bdh.data(), m, g + s->off_wo, s->qd, h, s->ld_qd, s->ld_h)) return rc;
+    if (int rc = wgrad(s, aa.data(), bdqkv.data(), m, g + s->off_wqkv, h, s->qkvw, s->ld_h, s->ld_qkv)) return rc;
+  }
+  s->head = (s->head + n) % c.max_inflight;
+  s->count -= n;
   return MLS_OK;
 }
 
@@ -470,9 +517,9 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
   if (id >= MLS_T_DY) {
     switch (id) {
       case MLS_T_DY: src = s->last_dy; cols = h; ld = s->last_dy_ld; break;
-      case MLS_T_DGU: src = s->dgu; cols = 2 * f; ld = s->ld_gu; break;
-      case MLS_T_DH: src = s->dh; cols = h; ld = s->ld_h; break;
-      case MLS_T_DQKV: src = s->dqkv; cols = s->qkvw; ld = s->ld_qkv; break;
+      case MLS_T_DGU: src = s->dgu + size_t(s->last_ws) * s->mb_gu; cols = 2 * f; ld = s->ld_gu; break;
+      case MLS_T_DH: src = s->dh + size_t(s->last_ws) * s->mb_h; cols = h; ld = s->ld_h; break;
+      case MLS_T_DQKV: src = s->dqkv + size_t(s->last_ws) * s->mb_qkv; cols = s->qkvw; ld = s->ld_qkv; break;
       default: return fail(MLS_E_RANGE, "unknown tensor id");
     }
     if (!s->last_dy) return fail(MLS_E_RANGE, "no backward has run yet");

@@ -74,13 +74,14 @@ def test_head_dim_128_gqa_single_kv_head():
 
 def test_uneven_layer_counts_and_interleaved_order_agree():
     """Entries forwarded with different layer counts (including zero) may be mixed; one-forward-one-backward
-    order gives the same result as all forwards then one backward, bit for bit."""
+    order gives the same y and dX bit for bit as all forwards then one backward; the weight gradients differ only
+    in fp32 summation order (one contraction over all micro-batches vs one per micro-batch)."""
     ks = [2, 0, 1]
     a = _check(TINY, ks, 1e-2)
     b = _check(TINY, ks, 1e-2, interleave=True)
     for u, v in zip(a[0] + a[1], b[0] + b[1]):
         assert np.array_equal(u, v)
-    assert np.array_equal(a[2], b[2])
+    assert rel_err(a[2], b[2]) < 1e-6
 
 
 def test_run_to_run_bitwise_determinism():
