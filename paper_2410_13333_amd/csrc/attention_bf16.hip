@@ -1,5 +1,5 @@
 // Causal grouped-query attention for bf16 storage on the gfx950 matrix cores: forward with online softmax,
-// backward as two kernels (dQ; dK and dV) that recompute the probabilities from the saved log-sum-exp.
+// backward as three kernels (dQ; dK; dV) that recompute the probabilities from the saved log-sum-exp.
 // Nothing of size S x S is ever written; no float atomics, so results are bitwise reproducible.
 //
 // Register-resident probabilities.  v_mfma_f32_32x32x16_bf16 leaves element (g*4+r) of lane l at
@@ -339,18 +339,24 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
   for (int t = 0; t < DT; t++) store_t(out, ldg, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
 }
 
-// ================================================================ backward: dK, dV
-// grid (n_kv, kv blocks of 128, b), longest first; wave w owns key rows j0 + 32w .. +31 and keeps their K and V as B operands.
-// Loops over the query heads of the group and the query blocks of 64 rows at or below the diagonal:
-// S = Q K^T and dP = dO V^T (lane column = key row), dV^T += dO^T P, dK^T += Q^T dS.
-template <int D>
-__global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv, int64_t ld,
-                                                              const bf16_t* __restrict__ d_o, int64_t ldo,
-                                                              const float* __restrict__ lse,
-                                                              const float* __restrict__ delta,
-                                                              bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
-                                                              int nkv) {
+// ================================================================ backward: dK and dV (one kernel each)
+// grid (n_kv, kv blocks of 128, b), longest first; wave w owns key rows j0 + 32w .. +31 and keeps their K (and V)
+// as B operands.  Loops over the query heads of the group and the query blocks of 64 rows at or below the
+// diagonal: S = Q K^T (lane column = key row), then
+//   WHAT = 0 (dK):  dP = dO V^T, dS = P (dP - delta), dK^T += Q^T dS
+//   WHAT = 1 (dV):  dV^T += dO^T P
+// Two kernels on purpose: with both accumulators in one kernel the register demand passes 256, the MFMAs fall
+// back to the accumulation-register form with hundreds of register copies per iteration, and only one workgroup
+// fits a CU.  Apart, S is recomputed once more but each kernel runs two workgroups per CU.
+template <int D, int WHAT>
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* __restrict__ qkv, int64_t ld,
+                                                                 const bf16_t* __restrict__ d_o, int64_t ldo,
+                                                                 const float* __restrict__ lse,
+                                                                 const float* __restrict__ delta,
+                                                                 bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
+                                                                 int nkv) {
   using TL = Tile<D>;
+  constexpr bool DKM = WHAT == 0;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
   __shared__ float stat[2][2][TR];                                       // [buffer][lse*log2e | delta]
@@ -361,15 +367,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
   const int j0 = kb * 128, jw = j0 + wave * 32, ji = jw + (lane & 31);
   const float scale = rsqrtf((float)D), sc = scale * LOG2E;
 
-  bf16x8 kf[KD], vf[KD];
+  bf16x8 kf[KD], vf[DKM ? KD : 1];
 #pragma unroll
   for (int kk = 0; kk < KD; kk++) {
     kf[kk] = gfrag(base, ld, ji, (nq + hk) * D + kk * 16 + (lane >> 5) * 8, ji < S);
-    vf[kk] = gfrag(base, ld, ji, (nq + nkv + hk) * D + kk * 16 + (lane >> 5) * 8, ji < S);
+    if (DKM) vf[kk] = gfrag(base, ld, ji, (nq + nkv + hk) * D + kk * 16 + (lane >> 5) * 8, ji < S);
   }
-  f32x16 dk[DT], dv[DT];
+  f32x16 acc[DT];
 #pragma unroll
-  for (int t = 0; t < DT; t++) { dk[t] = zero16(); dv[t] = zero16(); }
+  for (int t = 0; t < DT; t++) acc[t] = zero16();
 
   const int qb0 = j0 / TR, nqb = (S + TR - 1) / TR - qb0;  // query blocks per head
   const int niter = nqb > 0 ? nqb * grp : 0;
@@ -386,7 +392,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
     const uint32_t t = lds0 + (it & 1) * 2 * TL::BYTES;
     tq.dma(rq_src, ld, i0, hq * D, t, wave, live);
     td.dma(rd_src, ldo, i0, hq * D, t + TL::BYTES, wave, live);
-    if (live && threadIdx.x < 2 * TR) {
+    if (live && threadIdx.x < (DKM ? 2 : 1) * TR) {
       const int r = threadIdx.x & (TR - 1);
       const int64_t si = (int64_t(bi) * nq + hq) * S + i0 + r;
       rs = 0.f;
@@ -395,7 +401,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
   };
   // the statistics fetched by issue(it) are stored after the compute of iteration it-1 (or before the loop)
   auto put_stat = [&](int it) {
-    if (threadIdx.x < 2 * TR) stat[it & 1][threadIdx.x >> 6][threadIdx.x & (TR - 1)] = rs;
+    if (threadIdx.x < (DKM ? 2 : 1) * TR) stat[it & 1][threadIdx.x >> 6][threadIdx.x & (TR - 1)] = rs;
   };
   issue(0, niter > 0);
   put_stat(0);
@@ -407,50 +413,46 @@ __global__ __launch_bounds__(AT_THREADS) void attn_dkv_kernel(const bf16_t* __re
     if (i0 + TR - 1 >= jw) {  // wave-uniform: some query row at or below this wave's first key row
       const bf16_t* qs = lds[cur][0];
       const bf16_t* ds_ = lds[cur][1];
-      const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
+      f32x16 st[2], dp[DKM ? 2 : 1];
 #pragma unroll
-      for (int itl = 0; itl < 2; itl++) {  // one 32-row query tile at a time keeps the live registers down
-        f32x16 st = zero16(), dp = zero16();
+      for (int itl = 0; itl < 2; itl++) {
+        st[itl] = zero16();
+        if (DKM) dp[itl] = zero16();
 #pragma unroll
         for (int kk = 0; kk < KD; kk++) {
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp, 0, 0, 0);
-        }
-#pragma unroll
-        for (int g = 0; g < 4; g++) {
-          const int r0 = itl * 32 + (lane >> 5) * 4 + 8 * g;
-          const float4 l4 = *reinterpret_cast<const float4*>(&stat[cur][0][r0]);
-          const float4 d4 = *reinterpret_cast<const float4*>(&stat[cur][1][r0]);
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int rr = 0; rr < 4; rr++) {
-            const int e = g * 4 + rr;
-            float p = __builtin_amdgcn_exp2f(st[e] * sc - lv[rr]);
-            if (diag && (i0 + r0 + rr < ji || i0 + r0 + rr >= S)) p = 0.f;
-            st[e] = p;
-            dp[e] = p * (dp[e] - dv4[rr]);
-          }
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; s2++) {
-          const bf16x8 pf = acc_to_b(st, s2), df = acc_to_b(dp, s2);
-#pragma unroll
-          for (int t = 0; t < DT; t++) {
-            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ds_, t, itl * 2 + s2, lane), pf, dv[t], 0, 0, 0);
-            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(qs, t, itl * 2 + s2, lane), df, dk[t], 0, 0, 0);
-          }
+          st[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st[itl], 0, 0, 0);
+          if (DKM)
+            dp[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp[itl], 0, 0, 0);
         }
       }
+      const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
+#pragma unroll
+      for (int itl = 0; itl < 2; itl++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+          float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
+          if (diag && (i0 + r < ji || i0 + r >= S)) p = 0.f;
+          st[itl][e] = DKM ? p * (dp[itl][e] - stat[cur][1][r]) : p;  // dK consumes dS, dV consumes P
+        }
+      const bf16_t* tx = DKM ? qs : ds_;
+#pragma unroll
+      for (int itl = 0; itl < 2; itl++)
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+          const bf16x8 bf = acc_to_b(st[itl], s);
+#pragma unroll
+          for (int t = 0; t < DT; t++)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(tx, t, itl * 2 + s, lane), bf, acc[t], 0, 0, 0);
+        }
     }
     if (it + 1 < niter) put_stat(it + 1);
   }
   wait_dma();
   bf16_t* out = dqkv + int64_t(bi) * S * ldg;
 #pragma unroll
-  for (int t = 0; t < DT; t++) {
-    store_t(out, ldg, ji, (nq + hk) * D + t * 32, dk[t], scale, lane, ji < S);
-    store_t(out, ldg, ji, (nq + nkv + hk) * D + t * 32, dv[t], 1.f, lane, ji < S);
-  }
+  for (int t = 0; t < DT; t++)
+    store_t(out, ldg, ji, (DKM ? nq + hk : nq + nkv + hk) * D + t * 32, acc[t], DKM ? scale : 1.f, lane, ji < S);
 }
 
 }  // namespace
@@ -482,13 +484,17 @@ hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t
   if (d == 128) {
     hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
                        ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
-    hipLaunchKernelGGL(attn_dkv_kernel<128>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL((attn_dkv_kernel<128, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL((attn_dkv_kernel<128, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
   } else if (d == 64) {
     hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
                        ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
-    hipLaunchKernelGGL(attn_dkv_kernel<64>, gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL((attn_dkv_kernel<64, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+    hipLaunchKernelGGL((attn_dkv_kernel<64, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
   } else {
     return hipErrorInvalidValue;
   }
