@@ -14,6 +14,8 @@
 // LDS tiles are 64 rows x D columns, unpadded, with an XOR swizzle of the 16-byte chunks that makes both
 // access patterns bank-conflict free: ds_read_b128 of 16 consecutive rows at one column chunk, and the
 // transposing 8-byte reads of 4 consecutive rows x 64 bytes.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -196,18 +198,20 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
         for (int kk = 0; kk < KD; kk++)
           st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ks, jt, kk, lane), qf[kk], st[jt], 0, 0, 0);
       }
-      const bool diag = j0 + TR - 1 > qw;  // some pair may be masked
       float mx = -INFINITY;
+      auto scale_mask = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++)
+        for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-          float t = st[jt][e] * sc;
-          if (diag && j > qi) t = -INFINITY;
-          st[jt][e] = t;
-          mx = fmaxf(mx, t);
-        }
+          for (int e = 0; e < 16; e++) {
+            const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+            float t = st[jt][e] * sc;
+            if (decltype(MASK)::value && j > qi) t = -INFINITY;
+            st[jt][e] = t;
+            mx = fmaxf(mx, t);
+          }
+      };
+      if (j0 + TR - 1 > qw) scale_mask(std::true_type{}); else scale_mask(std::false_type{});  // some pair masked?
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m, mx);  // finite: block 0 always holds j = 0 <= i
       const float corr = __builtin_amdgcn_exp2f(m - mn);
@@ -312,6 +316,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
           dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(vs, jt, kk, lane), dof[kk], dp[jt], 0, 0, 0);
         }
       }
+      // (one code path with a uniform flag: two specialised paths push this kernel over 256 registers into spills)
       const bool diag = j0 + TR - 1 > qw;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
@@ -426,15 +431,31 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
         }
       }
       const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
+      if (DKM) {
+        // (one code path with a uniform flag: a separate mask-free path pushes this kernel over 256 registers)
 #pragma unroll
-      for (int itl = 0; itl < 2; itl++)
+        for (int itl = 0; itl < 2; itl++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-          float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
-          if (diag && (i0 + r < ji || i0 + r >= S)) p = 0.f;
-          st[itl][e] = DKM ? p * (dp[itl][e] - stat[cur][1][r]) : p;  // dK consumes dS, dV consumes P
-        }
+          for (int e = 0; e < 16; e++) {
+            const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+            float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
+            if (diag && (i0 + r < ji || i0 + r >= S)) p = 0.f;
+            st[itl][e] = p * (dp[itl][e] - stat[cur][1][r]);  // dS
+          }
+      } else {
+        auto softmax = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
+#pragma unroll
+          for (int itl = 0; itl < 2; itl++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+              const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+              float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
+              if (decltype(MASK)::value && (i0 + r < ji || i0 + r >= S)) p = 0.f;
+              st[itl][e] = p;
+            }
+        };
+        if (diag) softmax(std::true_type{}); else softmax(std::false_type{});
+      }
       const bf16_t* tx = DKM ? qs : ds_;
 #pragma unroll
       for (int itl = 0; itl < 2; itl++)
