@@ -106,17 +106,23 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
   }
 }
 
-// out[c] += sum_b partial[b][c]: 64 columns per workgroup, 4 row groups per column, fixed summation order
+// out[c] += sum_b partial[b][c]: 16 columns per workgroup, 16 row groups per column, fixed summation order
 __global__ __launch_bounds__(256) void colsum_add_kernel(const float* __restrict__ partial, float* __restrict__ out,
                                                          int nblocks, int h) {
-  __shared__ float red[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
+  __shared__ float red[16][17];
+  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
   float s = 0.f;
   if (c < h)
-    for (int b = grp; b < nblocks; b += 4) s += partial[int64_t(b) * h + c];
-  red[grp][threadIdx.x & 63] = s;
+    for (int b = grp; b < nblocks; b += 16) s += partial[int64_t(b) * h + c];
+  red[grp][cl] = s;
   __syncthreads();
-  if (grp == 0 && c < h) out[c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  if (grp == 0 && c < h) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; g++) t += red[g][cl];
+    out[c] += t;
+  }
 }
 
 // ---------------------------------------------------------------- rotary embedding, in place
@@ -269,7 +275,7 @@ hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int
 #undef BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 63) / 64), dim3(256), 0, st, partial, dgamma, nb, h);
+  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 15) / 16), dim3(256), 0, st, partial, dgamma, nb, h);
   return hipGetLastError();
 }
 

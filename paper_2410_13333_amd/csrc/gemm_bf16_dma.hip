@@ -333,13 +333,36 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
   return hipGetLastError();
 }
 
+// When the 256x256 tiles fill the 256 CUs a whole number of times plus a short remainder, the remainder would
+// still cost a full round.  Returns the number of leading columns (a multiple of 256) to run with 256x256 tiles
+// so that they fill whole rounds; the columns after them are run with 256x128 tiles, whose partial round costs
+// about half as much.  0 = do not split.
+int split_columns(int M, int N) {
+  const int tm = (M + 255) / 256, tn = (N + 255) / 256, tiles = tm * tn;
+  const int full = tiles / 256 * 256, rest = tiles - full;
+  if (full == 0 || rest == 0 || rest > 128) return 0;  // remainder above half a round: nothing to gain
+  const int n1_tiles = full / tm;
+  if (n1_tiles <= 0 || n1_tiles >= tn) return 0;
+  return n1_tiles * 256;
+}
+
 template <bool ATR, bool BTR, int EPI>
 hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
   // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
   // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.
-  if (big_tiles >= 192 && BTR) return launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+  if (big_tiles >= 192 && BTR) {
+    const int n1 = split_columns(M, N);
+    if (n1 > 0) {
+      hipError_t e = launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st);
+      if (e != hipSuccess) return e;
+      void* c2 = EPI == EPI_BF16 ? (void*)(static_cast<bf16_t*>(C) + n1) : (void*)(static_cast<float*>(C) + n1);
+      return launch<256, 128, 32, 4, ATR, BTR, EPI, true>(A, B + n1, c2, R ? R + n1 : nullptr, M, N - n1, K, lda, ldb, ldc,
+                                                          ldr, ab, bb, st);
+    }
+    return launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+  }
   if (big_tiles >= 192) return launch<256, 256, 64, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
   return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
 }
@@ -389,9 +412,20 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   sa.kseg = kseg;
   const uint32_t ab = uint32_t(int64_t(kseg) * lda * 2), bb = uint32_t(int64_t(kseg) * ldb * 2);
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192)
+  if (big_tiles >= 192) {
+    const int n1 = split_columns(M, N);
+    if (n1 > 0) {
+      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], C, nullptr, M, n1, kseg,
+                                                                                  lda, ldb, ldc, 0, ab, bb, st, &sa);
+      if (e != hipSuccess) return e;
+      for (int i = 0; i < nseg; i++) sa.b[i] += n1;
+      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], static_cast<float*>(C) + n1,
+                                                                          nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb,
+                                                                          st, &sa);
+    }
     return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
                                                                       ldc, 0, ab, bb, st, &sa);
+  }
   return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, false, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
                                                                      ldc, 0, ab, bb, st, &sa);
 }

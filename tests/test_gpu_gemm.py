@@ -7,7 +7,7 @@ from tests.helpers import rel_err, to_host64
 pytestmark = pytest.mark.gpu
 
 SHAPES = [(256, 768, 256), (256, 1376, 256), (256, 256, 688), (392, 520, 328), (8, 8, 8), (1024, 2048, 512),
-          (4096, 4096, 1024), (520, 4104, 264)]
+          (4096, 4096, 1024), (520, 4104, 264), (4096, 22016, 136)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
