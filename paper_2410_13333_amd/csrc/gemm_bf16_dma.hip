@@ -21,6 +21,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 enum { EPI_BF16 = 0, EPI_F32_ACC = 1 };
+enum { PIPE_PLAIN = 0, PIPE_SKEW = 1, PIPE_LATE = 2 };
 
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_byte), "v"(voff), "s"(rsrc)
@@ -115,7 +116,7 @@ struct ColTile {
   }
 };
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW, bool SEG>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE, bool SEG>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                        void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
@@ -189,8 +190,9 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = (SEG ? segs.nseg : 1) * ((kpiece + BK - 1) / BK);
+  constexpr int PRO = PIPE == PIPE_LATE ? NS : NS - 1;  // tiles in flight before the first MFMA
 #pragma unroll
-  for (int s = 0; s < NS - 1; s++) {
+  for (int s = 0; s < PRO; s++) {
 #pragma unroll
     for (int d = 0; d < LPT; d++) fire(d, s, s < nk);
     advance();
@@ -209,15 +211,15 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
     for (int j = 0; j < TN; j++)
       bfr[buf][j] = BTR ? BT_C::frag(sb, wn + j * 32, kk, lane) : BT_R::frag(sb, wn + j * 32, kk, lane);
   };
-  // one 16-wide k-substep: fire this substep's share of the next tile's DMA between the two halves of the MFMA
+  // one 16-wide k-substep; DMA instructions [d0, d1) of the prefetched tile go out between the rows of the MFMA
   // block (operands swapped: the lane ends up with 4 consecutive columns of one row)
-  auto mfma_block = [&](int kk, int pstage, bool prefetch) {
+  auto mfma_block = [&](int kk, int pstage, bool prefetch, int d0, int d1) {
+    const int per = (d1 - d0 + TM - 1) / TM;
 #pragma unroll
     for (int i = 0; i < TM; i++) {
-      if (i == TM / 2) {
 #pragma unroll
-        for (int d = kk * DPK; d < (kk + 1) * DPK && d < LPT; d++) fire(d, pstage, prefetch);
-      }
+      for (int d = d0 + ((i + TM / 2) % TM) * per; d < d0 + ((i + TM / 2) % TM + 1) * per && d < d1; d++)
+        fire(d, pstage, prefetch);
 #pragma unroll
       for (int j = 0; j < TN; j++)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
@@ -233,11 +235,11 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
     }
   };
   int stage = 0;
-  if (SKEW) {
+  if (PIPE == PIPE_SKEW) {
     // Skewed pipeline (needs NS >= 3 and an even number of substeps): the barrier at the top of iteration kt
     // publishes tile kt+1, so the first fragments of tile kt+1 are fetched during the last substep of tile kt
     // and no LDS latency is exposed behind the barrier.
-    static_assert(!SKEW || (NS >= 3 && KS % 2 == 0), "skewed pipeline needs 3 stages");
+    static_assert(PIPE != PIPE_SKEW || (NS >= 3 && KS % 2 == 0), "skewed pipeline needs 3 stages");
     wait_vmcnt<(NS - 2) * LPT>();
     __syncthreads();
     lfrag(smem, 0, 0);
@@ -251,11 +253,39 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int kk = 0; kk < KS; kk++) {
         __builtin_amdgcn_sched_barrier(0);
         if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1); else lfrag(smem + nstage * STAGE, 0, 0);
-        mfma_block(kk, pstage, prefetch);
+        mfma_block(kk, pstage, prefetch, kk * DPK, (kk + 1) * DPK < LPT ? (kk + 1) * DPK : LPT);
         interleave_hint();
       }
       advance();
       stage = nstage;
+    }
+  } else if (PIPE == PIPE_LATE) {
+    // Two stages, barrier BEFORE the last substep: by then every fragment of tile kt is in registers, so the
+    // barrier both retires tile kt's buffer (the DMA of tile kt+2 goes out right behind it and has a whole tile of
+    // MFMAs to land) and publishes tile kt+1, whose first fragments are fetched during the last substep of tile
+    // kt.  Same flight time as the plain two-stage loop, but no LDS latency exposed behind the barrier.
+    static_assert(PIPE != PIPE_LATE || (NS == 2 && KS % 2 == 0), "late-barrier pipeline is the two-stage form");
+    wait_vmcnt<LPT>();
+    __syncthreads();
+    lfrag(smem, 0, 0);
+    for (int kt = 0; kt < nk; kt++) {
+      const unsigned char* sa = smem + stage * STAGE;
+      const unsigned char* sn = smem + (stage ^ 1) * STAGE;
+#pragma unroll
+      for (int kk = 0; kk < KS - 1; kk++) {
+        __builtin_amdgcn_sched_barrier(0);
+        lfrag(sa, kk + 1, (kk + 1) & 1);
+        mfma_block(kk, 0, false, 0, 0);
+        interleave_hint();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt<0>();   // this wave's part of tile kt+1 has landed
+      __syncthreads();   // everyone's has, and nobody reads tile kt's buffer any more
+      lfrag(sn, 0, 0);
+      mfma_block(KS - 1, stage, kt + 2 < nk, 0, LPT);
+      interleave_hint();
+      advance();
+      stage ^= 1;
     }
   } else {
     for (int kt = 0; kt < nk; kt++) {
@@ -270,7 +300,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int kk = 0; kk < KS; kk++) {
         __builtin_amdgcn_sched_barrier(0);
         if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1);
-        mfma_block(kk, pstage, prefetch);
+        mfma_block(kk, pstage, prefetch, kk * DPK, (kk + 1) * DPK < LPT ? (kk + 1) * DPK : LPT);
         if (kk + 1 < KS) interleave_hint();
       }
       advance();
@@ -314,12 +344,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   }
 }
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, bool SKEW = false, bool SEG = false>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE = PIPE_PLAIN, bool SEG = false>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                   int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
                   const SegArgs* segs = nullptr) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
-  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, SKEW, SEG>;
+  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG>;
   SegArgs sa = {};
   if (segs) sa = *segs;
   static bool attr_set = false;
@@ -351,19 +381,23 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
   // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
-  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.
-  if (big_tiles >= 192 && BTR) {
+  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win (the late-barrier
+  // form of the two-stage loop measured slower than the plain one in every mode).
+  constexpr int BK = BTR ? 32 : 64, NS = BTR ? 4 : 2, PIPE = BTR ? PIPE_SKEW : PIPE_PLAIN;
+  if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st);
+      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st);
       if (e != hipSuccess) return e;
       void* c2 = EPI == EPI_BF16 ? (void*)(static_cast<bf16_t*>(C) + n1) : (void*)(static_cast<float*>(C) + n1);
-      return launch<256, 128, 32, 4, ATR, BTR, EPI, true>(A, B + n1, c2, R ? R + n1 : nullptr, M, N - n1, K, lda, ldb, ldc,
-                                                          ldr, ab, bb, st);
+      // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
+      const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
+      const uint32_t bb2 = BTR ? bb : uint32_t(int64_t(N - n1) * ldb * 2);
+      return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, c2, R ? R + n1 : nullptr, M, N - n1, K, lda, ldb, ldc,
+                                                            ldr, ab, bb2, st);
     }
-    return launch<256, 256, 32, 4, ATR, BTR, EPI, true>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
   }
-  if (big_tiles >= 192) return launch<256, 256, 64, 2, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
   return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
 }
 
@@ -415,18 +449,18 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], C, nullptr, M, n1, kseg,
+      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, n1, kseg,
                                                                                   lda, ldb, ldc, 0, ab, bb, st, &sa);
       if (e != hipSuccess) return e;
       for (int i = 0; i < nseg; i++) sa.b[i] += n1;
-      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], static_cast<float*>(C) + n1,
+      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], static_cast<float*>(C) + n1,
                                                                           nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb,
                                                                           st, &sa);
     }
-    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, true, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
+    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
                                                                       ldc, 0, ab, bb, st, &sa);
   }
-  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, false, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
+  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
                                                                      ldc, 0, ab, bb, st, &sa);
 }
 
