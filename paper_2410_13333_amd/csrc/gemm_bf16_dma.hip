@@ -21,7 +21,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 enum { EPI_BF16 = 0, EPI_F32_ACC = 1 };
-enum { PIPE_PLAIN = 0, PIPE_SKEW = 1, PIPE_LATE = 2 };
+enum { PIPE_PLAIN = 0, PIPE_SKEW = 1 };
 
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_byte), "v"(voff), "s"(rsrc)
@@ -190,9 +190,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = (SEG ? segs.nseg : 1) * ((kpiece + BK - 1) / BK);
-  constexpr int PRO = PIPE == PIPE_LATE ? NS : NS - 1;  // tiles in flight before the first MFMA
 #pragma unroll
-  for (int s = 0; s < PRO; s++) {
+  for (int s = 0; s < NS - 1; s++) {
 #pragma unroll
     for (int d = 0; d < LPT; d++) fire(d, s, s < nk);
     advance();
@@ -258,34 +257,6 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       }
       advance();
       stage = nstage;
-    }
-  } else if (PIPE == PIPE_LATE) {
-    // Two stages, barrier BEFORE the last substep: by then every fragment of tile kt is in registers, so the
-    // barrier both retires tile kt's buffer (the DMA of tile kt+2 goes out right behind it and has a whole tile of
-    // MFMAs to land) and publishes tile kt+1, whose first fragments are fetched during the last substep of tile
-    // kt.  Same flight time as the plain two-stage loop, but no LDS latency exposed behind the barrier.
-    static_assert(PIPE != PIPE_LATE || (NS == 2 && KS % 2 == 0), "late-barrier pipeline is the two-stage form");
-    wait_vmcnt<LPT>();
-    __syncthreads();
-    lfrag(smem, 0, 0);
-    for (int kt = 0; kt < nk; kt++) {
-      const unsigned char* sa = smem + stage * STAGE;
-      const unsigned char* sn = smem + (stage ^ 1) * STAGE;
-#pragma unroll
-      for (int kk = 0; kk < KS - 1; kk++) {
-        __builtin_amdgcn_sched_barrier(0);
-        lfrag(sa, kk + 1, (kk + 1) & 1);
-        mfma_block(kk, 0, false, 0, 0);
-        interleave_hint();
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      wait_vmcnt<0>();   // this wave's part of tile kt+1 has landed
-      __syncthreads();   // everyone's has, and nobody reads tile kt's buffer any more
-      lfrag(sn, 0, 0);
-      mfma_block(KS - 1, stage, kt + 2 < nk, 0, LPT);
-      interleave_hint();
-      advance();
-      stage ^= 1;
     }
   } else {
     for (int kt = 0; kt < nk; kt++) {
@@ -381,8 +352,8 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
   // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
-  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win (the late-barrier
-  // form of the two-stage loop measured slower than the plain one in every mode).
+  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.  Deeper pipelines and a two-stage loop
+  // with its barrier ahead of the last substep all measured within noise of these or slower.
   constexpr int BK = BTR ? 32 : 64, NS = BTR ? 4 : 2, PIPE = BTR ? PIPE_SKEW : PIPE_PLAIN;
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
