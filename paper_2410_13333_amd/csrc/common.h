@@ -42,6 +42,32 @@ __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
   reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
   reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
 }
+// ---- 4-element bf16 (8-byte) loads and stores
+__device__ __forceinline__ void load4(const bf16_t* p, float (&v)[4]) {
+  const uint2 raw = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(raw.x << 16);
+  v[1] = __uint_as_float(raw.x & 0xffff0000u);
+  v[2] = __uint_as_float(raw.y << 16);
+  v[3] = __uint_as_float(raw.y & 0xffff0000u);
+}
+__device__ __forceinline__ void store4(bf16_t* p, const float (&v)[4]) {
+  uint2 raw;
+  raw.x = pack_bf16x2(v[0], v[1]);
+  raw.y = pack_bf16x2(v[2], v[3]);
+  *reinterpret_cast<uint2*>(p) = raw;
+}
+__device__ __forceinline__ float round_bf16(float v) { return (float)(bf16_t)v; }
+__device__ __forceinline__ float sigmoidf_(float g) { return 1.f / (1.f + __expf(-g)); }
+
+// ---- gate/up column order.  Public: [gate 0..f) | up 0..f)].  Interleaved (internal, used when the SwiGLU is fused
+// into the contractions around it; needs f % 32 == 0): 32 gate columns, then the 32 up columns of the same indices,
+// and so on, so that a lane of the contraction's epilogue holds a gate and its up.
+__host__ __device__ __forceinline__ int gu_public_col(int n, int f) { return ((n >> 5) & 1) * f + (n >> 6) * 32 + (n & 31); }
+__host__ __device__ __forceinline__ int gu_interleaved_col(int c, int f) {
+  const int w = c >= f, r = c - w * f;
+  return (r >> 5) * 64 + w * 32 + (r & 31);
+}
+
 __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ void from_f32(bf16_t& d, float v) { d = (bf16_t)v; }

@@ -155,7 +155,6 @@ __global__ __launch_bounds__(EW_THREADS) void rope_kernel(T* __restrict__ u, con
 }
 
 // ---------------------------------------------------------------- SwiGLU
-__device__ __forceinline__ float sigmoidf_(float g) { return 1.f / (1.f + __expf(-g)); }
 
 template <typename T>
 __global__ __launch_bounds__(EW_THREADS) void swiglu_fwd_kernel(const T* __restrict__ gu, int64_t ld_gu,
@@ -174,7 +173,8 @@ __global__ __launch_bounds__(EW_THREADS) void swiglu_fwd_kernel(const T* __restr
   store8(z + t * ld_z + c * 8, o);
 }
 
-template <typename T>
+// IL: gu and dgu are in the interleaved gate/up column order (32 gates, their 32 ups, ...), else [gates | ups]
+template <typename T, bool IL>
 __global__ __launch_bounds__(EW_THREADS) void swiglu_bwd_kernel(const T* __restrict__ dz, int64_t ld_dz,
                                                                 const T* __restrict__ gu, int64_t ld_gu,
                                                                 T* __restrict__ dgu, int64_t ld_dgu, int64_t total,
@@ -183,19 +183,20 @@ __global__ __launch_bounds__(EW_THREADS) void swiglu_bwd_kernel(const T* __restr
   if (id >= total) return;
   const int cpr = f >> 3;
   const int64_t t = id / cpr;
-  const int c = int(id % cpr);
+  const int c = int(id % cpr) * 8;
+  const int cg = IL ? (c >> 5) * 64 + (c & 31) : c, cu = IL ? cg + 32 : f + c;
   float g[8], u[8], d[8], og[8], ou[8];
-  load8(gu + t * ld_gu + c * 8, g);
-  load8(gu + t * ld_gu + f + c * 8, u);
-  load8(dz + t * ld_dz + c * 8, d);
+  load8(gu + t * ld_gu + cg, g);
+  load8(gu + t * ld_gu + cu, u);
+  load8(dz + t * ld_dz + c, d);
 #pragma unroll
   for (int e = 0; e < 8; e++) {
     const float s = sigmoidf_(g[e]);
     og[e] = d[e] * u[e] * s * (1.f + g[e] * (1.f - s));
     ou[e] = d[e] * g[e] * s;
   }
-  store8(dgu + t * ld_dgu + c * 8, og);
-  store8(dgu + t * ld_dgu + f + c * 8, ou);
+  store8(dgu + t * ld_dgu + cg, og);
+  store8(dgu + t * ld_dgu + cu, ou);
 }
 
 // ---------------------------------------------------------------- weight generator (counter-based, fp64 Box-Muller)
@@ -223,7 +224,7 @@ __device__ __forceinline__ void put(float* p, double v) { *p = (float)v; }
 template <typename T>
 __global__ __launch_bounds__(EW_THREADS) void fill_normal_kernel(T* __restrict__ out, int64_t n, int64_t cols,
                                                                  int64_t ld, uint64_t stream, double scale,
-                                                                 double offset) {
+                                                                 double offset, int gu_f) {
   const int64_t i = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;  // flat index in the dense (public) layout
   if (i >= n) return;
   const uint64_t c = stream + 2ull * (uint64_t)i;
@@ -231,7 +232,22 @@ __global__ __launch_bounds__(EW_THREADS) void fill_normal_kernel(T* __restrict__
   const double u1 = ((double)(r1 >> 11) + 1.0) * 0x1p-53;
   const double u2 = (double)(r2 >> 11) * 0x1p-53;
   const double z = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
-  put(out + (i / cols) * ld + (i % cols), offset + scale * z);
+  const int64_t col = i % cols;  // gu_f > 0: the tensor is stored in the interleaved gate/up column order
+  put(out + (i / cols) * ld + (gu_f > 0 ? gu_interleaved_col(int(col), gu_f) : col), offset + scale * z);
+}
+
+// dst <- src with the columns of a [rows, 2f] matrix moved between the public and the interleaved gate/up order
+// (8 columns per thread; blocks of 32 columns move as a whole)
+__global__ __launch_bounds__(EW_THREADS) void gu_permute_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
+                                                                bf16_t* __restrict__ dst, int64_t ld_dst,
+                                                                int64_t total, int f, bool to_interleaved) {
+  const int64_t id = int64_t(blockIdx.x) * EW_THREADS + threadIdx.x;
+  if (id >= total) return;
+  const int cpr = f >> 2;  // 16-byte chunks per row of 2f columns
+  const int64_t t = id / cpr;
+  const int c = int(id % cpr) * 8, ci = gu_interleaved_col(c, f);
+  const uint4 v = *reinterpret_cast<const uint4*>(src + t * ld_src + (to_interleaved ? c : ci));
+  *reinterpret_cast<uint4*>(dst + t * ld_dst + (to_interleaved ? ci : c)) = v;
 }
 
 inline int blocks_for(int64_t n) { return int((n + EW_THREADS - 1) / EW_THREADS); }
@@ -305,20 +321,33 @@ hipError_t swiglu_fwd(int dt, const void* gu, int64_t ld_gu, void* z, int64_t ld
 }
 
 hipError_t swiglu_bwd(int dt, const void* dz, int64_t ld_dz, const void* gu, int64_t ld_gu, void* dgu, int64_t ld_dgu,
-                      int T, int f, hipStream_t st) {
+                      int T, int f, hipStream_t st, bool interleaved) {
   const int64_t total = int64_t(T) * (f >> 3);
   if (total == 0) return hipSuccess;
-  if (dt == DT_BF16)
-    hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)dz,
-                       ld_dz, (const bf16_t*)gu, ld_gu, (bf16_t*)dgu, ld_dgu, total, f);
+  if (interleaved && (dt != DT_BF16 || f % 32)) return hipErrorInvalidValue;
+  if (interleaved)
+    hipLaunchKernelGGL((swiglu_bwd_kernel<bf16_t, true>), dim3(blocks_for(total)), dim3(EW_THREADS), 0, st,
+                       (const bf16_t*)dz, ld_dz, (const bf16_t*)gu, ld_gu, (bf16_t*)dgu, ld_dgu, total, f);
+  else if (dt == DT_BF16)
+    hipLaunchKernelGGL((swiglu_bwd_kernel<bf16_t, false>), dim3(blocks_for(total)), dim3(EW_THREADS), 0, st,
+                       (const bf16_t*)dz, ld_dz, (const bf16_t*)gu, ld_gu, (bf16_t*)dgu, ld_dgu, total, f);
   else
-    hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const float*)dz,
-                       ld_dz, (const float*)gu, ld_gu, (float*)dgu, ld_dgu, total, f);
+    hipLaunchKernelGGL((swiglu_bwd_kernel<float, false>), dim3(blocks_for(total)), dim3(EW_THREADS), 0, st,
+                       (const float*)dz, ld_dz, (const float*)gu, ld_gu, (float*)dgu, ld_dgu, total, f);
+  return hipGetLastError();
+}
+
+hipError_t gu_permute(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int f,
+                      bool to_interleaved, hipStream_t st) {
+  const int64_t total = rows * (f >> 2);
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(gu_permute_kernel, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)src, ld_src,
+                     (bf16_t*)dst, ld_dst, total, f, to_interleaved);
   return hipGetLastError();
 }
 
 hipError_t fill_normal(int dt, void* out, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, uint32_t tensor,
-                       uint32_t layer, double scale, double offset, hipStream_t st) {
+                       uint32_t layer, double scale, double offset, hipStream_t st, int gu_f) {
   const int64_t n = rows * cols;
   if (n == 0) return hipSuccess;
   auto mixh = [](uint64_t z) {
@@ -330,10 +359,10 @@ hipError_t fill_normal(int dt, void* out, int64_t rows, int64_t cols, int64_t ld
   const uint64_t stream = mixh(mixh(seed) ^ ((uint64_t(tensor) << 32) | layer));
   if (dt == DT_BF16)
     hipLaunchKernelGGL(fill_normal_kernel<bf16_t>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (bf16_t*)out, n, cols,
-                       ld, stream, scale, offset);
+                       ld, stream, scale, offset, gu_f);
   else
     hipLaunchKernelGGL(fill_normal_kernel<float>, dim3(blocks_for(n)), dim3(EW_THREADS), 0, st, (float*)out, n, cols, ld,
-                       stream, scale, offset);
+                       stream, scale, offset, gu_f);
   return hipGetLastError();
 }
 

@@ -20,12 +20,23 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-enum { EPI_BF16 = 0, EPI_F32_ACC = 1 };
+// Epilogues.  EPI_BF16: C = acc (+ R), bf16.  EPI_F32_ACC: C += acc, fp32; with `xf` > 0 the columns are the
+// gate/up-interleaved order and are written to their public places (see gu_public_col).  EPI_SWIGLU: N = 2f
+// interleaved columns [gate | up]; C receives both (bf16) and X[row][f] their SwiGLU product.  (The SwiGLU backward
+// as an epilogue of the dZ contraction was measured slower than a separate kernel: the epilogue's extra reads are
+// fully exposed with one workgroup per CU.)
+enum { EPI_BF16 = 0, EPI_F32_ACC = 1, EPI_SWIGLU = 2 };
 enum { PIPE_PLAIN = 0, PIPE_SKEW = 1 };
 
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_byte), "v"(voff), "s"(rsrc)
                : "memory");
+}
+// orders this wave's LDS accesses before the call against those after it (the wave exchanges data with itself)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -121,6 +132,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
                                                        void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
                                                        int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m,
+                                                       int col0, void* __restrict__ Xv, int64_t ldx, int xf,
                                                        SegArgs segs) {
   using AT_R = RowTile<BM, BK>;
   using AT_C = ColTile<BM, BK>;
@@ -280,45 +292,116 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   }
   wait_vmcnt<0>();  // nothing of this wave may still be writing LDS when it leaves
 
-  // Epilogue.  Element (g*4 + r) of lane l is C[row l%32][col (l/32)*4 + 8g + r] of its 32x32 tile.
+  // ---- Epilogue.  Element (g*4 + e) of lane l is C[row l%32][col (l/32)*4 + 8g + e] of its 32x32 tile: a store
+  // straight from the accumulators would touch 32 rows with 16 bytes each.  Instead each wave passes its tile, 32
+  // rows at a time, through its own 16 KiB of the (now free) LDS and moves whole rows to and from memory (bf16
+  // epilogues): lane l
+  // handles the 16-byte chunk l % NCH of row l / NCH.  The staging rows are XOR-swizzled by chunk so that both
+  // access patterns spread over all banks.  `col0` is the column of the whole problem at which this launch's
+  // column 0 sits (a launch may cover a column range).
+  __syncthreads();  // every wave has read its last fragments and every DMA has landed
+  unsigned char* ws = smem + wave * 16384;
+  constexpr int CW = BN / 2;                          // columns of a wave tile
+  constexpr int RB = CW * 2, NCH = RB / 16;           // bytes and 16-byte chunks per staged row (bf16)
+  constexpr int RPI = 64 / NCH, NT = 32 / RPI;        // rows per whole-wave access, accesses per 32 rows
+  const int crow = lane / NCH, cch = lane % NCH;      // this lane's row and chunk in a whole-wave access
+  const int r32 = lane & 31, hi = lane >> 5;
+  const bool col_ok = n0 + wn + cch * 8 < N;        // N is a multiple of 8
+  const int ccol = col0 + n0 + wn + cch * 8;        // first column of this lane's chunk, in the whole problem
+  auto stage_at = [&](int row, int chunk) { return ws + row * RB + ((chunk ^ (row & (NCH - 1))) << 4); };
 #pragma unroll
   for (int i = 0; i < TM; i++) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row >= M) continue;
+    const int row0 = m0 + wm + i * 32;
+    if (EPI == EPI_F32_ACC) {
+      // C += acc straight from the accumulator layout (16 bytes per lane, read and written by the same lane);
+      // staging this one through LDS measured slower
+      const int row = row0 + r32;
+      if (row < M) {
 #pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int g = 0; g < 4; g++) {
-        const int col = n0 + wn + j * 32 + (lane >> 5) * 4 + 8 * g;
-        if (col >= N) continue;
-        const int64_t off = int64_t(row) * ldc + col;
-        float v[4] = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-        if (EPI == EPI_BF16) {
-          if (R) {
-            const uint2 rr = *reinterpret_cast<const uint2*>(R + int64_t(row) * ldr + col);
-            v[0] += __uint_as_float(rr.x << 16);
-            v[1] += __uint_as_float(rr.x & 0xffff0000u);
-            v[2] += __uint_as_float(rr.y << 16);
-            v[3] += __uint_as_float(rr.y & 0xffff0000u);
-          }
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + off) = o;
-        } else {
-          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + off);
+        for (int q = 0; q < TN * 4; q++) {
+          const int j = q >> 2, g = q & 3, col = n0 + wn + j * 32 + hi * 4 + 8 * g;
+          if (col >= N) continue;
+          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + int64_t(row) * ldc +
+                                                (xf > 0 ? gu_public_col(col0 + col, xf) : col0 + col));
           float4 t = *c;
-          t.x += v[0]; t.y += v[1]; t.z += v[2]; t.w += v[3];
+          t.x += acc[i][j][g * 4]; t.y += acc[i][j][g * 4 + 1]; t.z += acc[i][j][g * 4 + 2]; t.w += acc[i][j][g * 4 + 3];
           *c = t;
         }
       }
+    } else {
+      if (EPI == EPI_BF16 && R) {  // residual rows -> LDS
+#pragma unroll
+        for (int t = 0; t < NT; t++) {
+          const int lrow = t * RPI + crow, row = row0 + lrow;
+          uint4 rr = make_uint4(0, 0, 0, 0);
+          if (row < M && col_ok) rr = *reinterpret_cast<const uint4*>(R + int64_t(row) * ldr + ccol);
+          *reinterpret_cast<uint4*>(stage_at(lrow, cch)) = rr;
+        }
+        wave_lds_sync();
+      }
+      // combine in the accumulator layout, in place
+      constexpr int ZRB = CW, ZNCH = ZRB / 16;  // SwiGLU product: half as many columns, staged behind the 8 KiB
+      unsigned char* wz = ws + 8192;
+#pragma unroll
+      for (int q = 0; q < TN * 4; q++) {
+        const int j = q >> 2, g = q & 3;
+        unsigned char* p = stage_at(r32, 4 * j + g) + hi * 8;
+        float v[4] = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+        if (EPI == EPI_BF16 && R) {
+          const uint2 rr = *reinterpret_cast<const uint2*>(p);
+          v[0] += __uint_as_float(rr.x << 16);
+          v[1] += __uint_as_float(rr.x & 0xffff0000u);
+          v[2] += __uint_as_float(rr.y << 16);
+          v[3] += __uint_as_float(rr.y & 0xffff0000u);
+        }
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]);
+        o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(p) = o;
+        if (EPI == EPI_SWIGLU && !(j & 1)) {
+          // 32-column blocks alternate gate, up: tile j (even) holds the gates of the ups in tile j + 1.  The
+          // product is formed from the stored (rounded) values, like a separate kernel reading them back.
+          float z[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const float gr = round_bf16(v[e]), ur = round_bf16(acc[i][j | 1][g * 4 + e]);
+            z[e] = gr * sigmoidf_(gr) * ur;
+          }
+          uint2 zo;
+          zo.x = pack_bf16x2(z[0], z[1]);
+          zo.y = pack_bf16x2(z[2], z[3]);
+          const int zc = 4 * (j >> 1) + g;
+          *reinterpret_cast<uint2*>(wz + r32 * ZRB + ((zc ^ (r32 & (ZNCH - 1))) << 4) + hi * 8) = zo;
+        }
+      }
+      wave_lds_sync();
+#pragma unroll
+      for (int t = 0; t < NT; t++) {
+        const int lrow = t * RPI + crow, row = row0 + lrow;
+        const uint4 o = *reinterpret_cast<const uint4*>(stage_at(lrow, cch));
+        if (row < M && col_ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(Cv) + int64_t(row) * ldc + ccol) = o;
+      }
+      if (EPI == EPI_SWIGLU) {
+        constexpr int ZRPI = 64 / ZNCH, ZNT = 32 / ZRPI;
+        const int zrow = lane / ZNCH, zch = lane % ZNCH;
+        const int zcol = ((col0 + n0 + wn) >> 1) + zch * 8;  // product column of this lane's chunk
+        const bool z_ok = n0 + wn + zch * 16 < N;
+#pragma unroll
+        for (int t = 0; t < ZNT; t++) {
+          const int lrow = t * ZRPI + zrow, row = row0 + lrow;
+          const uint4 o = *reinterpret_cast<const uint4*>(wz + lrow * ZRB + ((zch ^ (lrow & (ZNCH - 1))) << 4));
+          if (row < M && z_ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(Xv) + int64_t(row) * ldx + zcol) = o;
+        }
+      }
+      wave_lds_sync();
+    }
   }
 }
 
 template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE = PIPE_PLAIN, bool SEG = false>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                   int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
-                  const SegArgs* segs = nullptr) {
+                  const SegArgs* segs = nullptr, int col0 = 0, void* X = nullptr, int64_t ldx = 0, int xf = 0) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG>;
   SegArgs sa = {};
@@ -330,7 +413,8 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
     attr_set = true;
   }
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm, sa);
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm,
+                     col0, X, ldx, xf, sa);
   return hipGetLastError();
 }
 
@@ -347,29 +431,41 @@ int split_columns(int M, int N) {
   return n1_tiles * 256;
 }
 
+// Extra operands of the fused epilogues (see the EPI_* list)
+struct Extra {
+  void* X = nullptr;
+  int64_t ldx = 0;
+  int xf = 0;
+};
+
+// A problem may run as two launches over column ranges; they never offset C, R or X: the kernel adds `col0`, the
+// first column of its range, to its epilogue columns
 template <bool ATR, bool BTR, int EPI>
 hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
-                    int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st) {
+                    int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st,
+                    const Extra& x = Extra()) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
   // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
-  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.  Deeper pipelines and a two-stage loop
-  // with its barrier ahead of the last substep all measured within noise of these or slower.
+  // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.  Deeper pipelines
+  // and a two-stage loop with its barrier ahead of the last substep all measured within noise of these or slower.
   constexpr int BK = BTR ? 32 : 64, NS = BTR ? 4 : 2, PIPE = BTR ? PIPE_SKEW : PIPE_PLAIN;
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st);
+      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
+                                                                    nullptr, 0, x.X, x.ldx, x.xf);
       if (e != hipSuccess) return e;
-      void* c2 = EPI == EPI_BF16 ? (void*)(static_cast<bf16_t*>(C) + n1) : (void*)(static_cast<float*>(C) + n1);
       // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
       const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
       const uint32_t bb2 = BTR ? bb : uint32_t(int64_t(N - n1) * ldb * 2);
-      return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, c2, R ? R + n1 : nullptr, M, N - n1, K, lda, ldb, ldc,
-                                                            ldr, ab, bb2, st);
+      return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st,
+                                                            nullptr, n1, x.X, x.ldx, x.xf);
     }
-    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
+                                                          x.X, x.ldx, x.xf);
   }
-  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st);
+  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0, x.X,
+                                                 x.ldx, x.xf);
 }
 
 }  // namespace
@@ -405,9 +501,9 @@ bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb) { return gemm_bf16_
 // C[M,N] += sum_i A_i[kseg,M]^T * B_i[kseg,N] (fp32 C), the contraction of all pieces accumulated in registers and
 // added to C once: the weight gradient of several micro-batches in one launch.  nseg <= 16.
 hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
-                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st) {
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f) {
   if (M == 0 || N == 0 || nseg == 0 || kseg == 0) return hipSuccess;
-  if (nseg > MAX_SEGS) return hipErrorInvalidValue;
+  if (nseg > MAX_SEGS || (gu_f > 0 && (gu_f % 32 || N != 2 * gu_f))) return hipErrorInvalidValue;
   SegArgs sa = {};
   for (int i = 0; i < nseg; i++) {
     sa.a[i] = static_cast<const bf16_t*>(A[i]);
@@ -420,19 +516,36 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, n1, kseg,
-                                                                                  lda, ldb, ldc, 0, ab, bb, st, &sa);
+      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
+          sa.a[0], sa.b[0], C, nullptr, M, n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0, gu_f);
       if (e != hipSuccess) return e;
       for (int i = 0; i < nseg; i++) sa.b[i] += n1;
-      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], static_cast<float*>(C) + n1,
-                                                                          nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb,
-                                                                          st, &sa);
+      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
+          sa.a[0], sa.b[0], C, nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, n1, nullptr, 0, gu_f);
     }
-    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
-                                                                      ldc, 0, ab, bb, st, &sa);
+    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
+                                                                              ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0,
+                                                                              gu_f);
   }
-  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda, ldb,
-                                                                     ldc, 0, ab, bb, st, &sa);
+  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
+                                                                             ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0,
+                                                                             gu_f);
+}
+
+bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw) {
+  return f > 0 && f % 32 == 0 && gemm_bf16_dma_ok(GEMM_NN, M, 2 * f, K, lda, ldw);
+}
+
+hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int f, int K, int64_t lda,
+                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st) {
+  if (M == 0 || f == 0) return hipSuccess;
+  if (f % 32 || !gemm_bf16_dma_ok(GEMM_NN, M, 2 * f, K, lda, ldw)) return hipErrorInvalidValue;
+  Extra x;
+  x.X = Z;
+  x.ldx = ldz;
+  return dispatch<false, true, EPI_SWIGLU>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), GU, nullptr, M,
+                                           2 * f, K, lda, ldw, ldgu, 0, uint32_t(int64_t(M) * lda * 2),
+                                           uint32_t(int64_t(K) * ldw * 2), st, x);
 }
 
 }  // namespace mls

@@ -21,8 +21,15 @@ hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const 
 // weight gradient of several micro-batches in one launch: C[M,N] += sum_i A_i[kseg,M]^T * B_i[kseg,N], C fp32,
 // at most 16 pieces, all with the same strides; true if the operands fit the DMA path's 31-bit offsets
 bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb);
+// gu_f > 0: the N = 2 gu_f columns of the B pieces are in the interleaved gate/up order and C is in the public one
 hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
-                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st);
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f = 0);
+// SwiGLU fused into the gate/up contraction (bf16, f % 32 == 0, DMA path).  Interleaved gate/up column order:
+// 32 gate columns, the 32 up columns of the same indices, and so on (gu_interleaved_col in common.h).
+//   GU[M, 2f] = A[M,K] W[K, 2f] (W and GU interleaved), Z[M, f] = silu(gate) * up
+bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw);
+hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int f, int K, int64_t lda,
+                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st);
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st);
 
@@ -42,11 +49,15 @@ hipError_t rope_inplace(int dt, void* u, const float* cos_tab, const float* sin_
                         int64_t ld, float sign, hipStream_t st);
 hipError_t swiglu_fwd(int dt, const void* gu, int64_t ld_gu, void* z, int64_t ld_z, int T, int f, hipStream_t st);
 hipError_t swiglu_bwd(int dt, const void* dz, int64_t ld_dz, const void* gu, int64_t ld_gu, void* dgu, int64_t ld_dgu,
-                      int T, int f, hipStream_t st);
+                      int T, int f, hipStream_t st, bool interleaved = false);  // interleaved: gu, dgu in that order
 // weights from the counter-based generator: element (r, c) of a rows x cols tensor stored with row stride ld is
 // offset + scale*z(seed, tensor, layer, r*cols + c), rounded once
 hipError_t fill_normal(int dt, void* out, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, uint32_t tensor,
-                       uint32_t layer, double scale, double offset, hipStream_t st);
+                       uint32_t layer, double scale, double offset, hipStream_t st, int gu_f = 0);
+// gu_f > 0 above: a [rows, 2 gu_f] gate/up tensor is written in the interleaved column order.  gu_permute moves a
+// bf16 [rows, 2f] matrix between the public and the interleaved column order.
+hipError_t gu_permute(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int f,
+                      bool to_interleaved, hipStream_t st);
 
 // ---- attention (attention_bf16.hip, attention_f32.hip).  qkv: [T, q_dim + 2 kv_dim] rows = q heads | k heads | v heads
 // (rotary already applied); o: [T, q_dim]; lse: natural-log softmax denominators [b, n_q, S] fp32.

@@ -82,6 +82,9 @@ struct mls_stage {
   // Internal row strides (elements).  Widths whose byte size is a multiple of 512 get 64 extra elements so that
   // the rows of a GEMM tile do not all fall on the same L2 / memory channel.
   int64_t ld_h, ld_qkv, ld_qd, ld_gu, ld_f;
+  // SwiGLU runs as the epilogue of the gate/up contraction; w_gu, gu and dgu are then kept in the interleaved
+  // gate/up column order (bf16 storage, ffn % 32 == 0)
+  bool fuse_gu = false;
   size_t ilayer_params;  // elements per layer, internal (row-padded) layout
   size_t ioff_g1, ioff_wqkv, ioff_wo, ioff_g2, ioff_wgu, ioff_wd;
   char* params = nullptr;  // storage type, internal layout
@@ -168,7 +171,7 @@ int init_weights(mls_stage* s, uint64_t seed) {
   for (int l = 0; l < s->c.max_layers; l++)
     for (auto& e : t)
       HIP_TRY(mls::fill_normal(s->dt, s->param(l, e.ioff), e.rows, e.cols, e.ld, seed, e.tid, (uint32_t)l, e.scale,
-                               e.offset, s->st));
+                               e.offset, s->st, e.tid == MLS_P_WGU && s->fuse_gu ? s->c.ffn : 0));
   return MLS_OK;
 }
 
@@ -195,8 +198,12 @@ int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
   LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->ioff_wo), e + L.h, e + L.x, T, h, s->qd, lo, lh, lh, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.h, lh, s->param(layer, s->ioff_g2), e + L.b, lh, (float*)(e + L.r2), T, h,
                                     c.rms_eps, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->ioff_wgu), e + L.gu, nullptr, T, 2 * f, h, lh, lg, lg));
-  LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, lg, e + L.z, lf, T, f, s->st));
+  if (s->fuse_gu) {
+    LAUNCH(CLS_GEMM_NN, mls::gemm_bf16_swiglu(e + L.b, s->param(layer, s->ioff_wgu), e + L.gu, e + L.z, T, f, h, lh, lg, lg, lf, s->st));
+  } else {
+    LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.b, s->param(layer, s->ioff_wgu), e + L.gu, nullptr, T, 2 * f, h, lh, lg, lg));
+    LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, lg, e + L.z, lf, T, f, s->st));
+  }
   // `out` is either the next layer's x (row stride ld_h) or the caller's dense y
   LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->ioff_wd), out, e + L.h, T, h, f, lf, lh, ld_out, lh));
   return MLS_OK;
@@ -217,7 +224,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* e, int w, const voi
   char* dqkv = s->dqkv + size_t(w) * s->mb_qkv;
   // MLP
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->ioff_wd), s->dz, nullptr, T, f, h, ld_dy, lh, lf));
-  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st));
+  LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st, s->fuse_gu));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
                                     dy, ld_dy, dh, lh, g + s->off_g2, s->partial, T, h, s->st));
@@ -236,10 +243,10 @@ int layer_backward_data(mls_stage* s, int layer, const char* e, int w, const voi
 // C[M,N] += sum_i A_i[T,M]^T B_i[T,N] over n micro-batches (fp32 C): one launch per 16 micro-batches on the bf16
 // DMA path, one launch per micro-batch otherwise
 int wgrad(mls_stage* s, const void* const* A, const void* const* B, int n, float* C, int M, int N, int64_t lda,
-          int64_t ldb) {
-  if (s->dt == mls::DT_BF16 && mls::gemm_tn_segments_ok(s->T, lda, ldb)) {
+          int64_t ldb, int gu_f = 0) {
+  if (s->dt == mls::DT_BF16 && mls::gemm_tn_segments_ok(s->T, lda, ldb)) {  // always true when gu_f > 0
     for (int i = 0; i < n; i += 16)
-      LAUNCH(CLS_GEMM_TN, mls::gemm_bf16_tn_segments(A + i, B + i, n - i < 16 ? n - i : 16, C, M, N, s->T, lda, ldb, N, s->st));
+      LAUNCH(CLS_GEMM_TN, mls::gemm_bf16_tn_segments(A + i, B + i, n - i < 16 ? n - i : 16, C, M, N, s->T, lda, ldb, N, s->st, gu_f));
   } else {
     for (int i = 0; i < n; i++) LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, A[i], B[i], C, nullptr, M, N, s->T, lda, ldb, N));
   }
@@ -296,6 +303,8 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   s->ioff_wgu = s->ioff_g2 + h;
   s->ioff_wd = s->ioff_wgu + h * s->ld_gu;
   s->ilayer_params = s->ioff_wd + f * s->ld_h;
+  s->fuse_gu = s->dt == mls::DT_BF16 && mls::gemm_swiglu_ok(s->T, c.ffn, c.hidden, s->ld_h, s->ld_gu) &&
+               mls::gemm_tn_segments_ok(s->T, s->ld_h, s->ld_gu);
 
   LayerStash& L = s->ls;
   size_t o = 0;
@@ -370,6 +379,7 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
 
 int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y) {
   if (!s || !x || !y) return fail(MLS_E_NULL, "mls_stage_forward: null argument");
+  if ((uintptr_t(x) | uintptr_t(y)) & 15) return fail(MLS_E_CONFIG, "mls_stage_forward: x and y must be 16-byte aligned");
   if (k_layers < 0 || k_layers > s->c.max_layers) return fail(MLS_E_RANGE, "k_layers outside [0, max_layers]");
   if (s->count >= s->c.max_inflight) return fail(MLS_E_STASH, "stash full: max_inflight micro-batches already forwarded");
   const size_t act = size_t(s->T) * s->c.hidden * s->es;
@@ -394,6 +404,8 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
   if (n < 0) return fail(MLS_E_RANGE, "n_microbatches must be >= 0");
   if (n == 0) return MLS_OK;
   if (!dY || !dX || !grads) return fail(MLS_E_NULL, "mls_stage_backward: null argument");
+  if ((uintptr_t(dY) | uintptr_t(dX) | uintptr_t(grads)) & 15)
+    return fail(MLS_E_CONFIG, "mls_stage_backward: dY, dX and grads must be 16-byte aligned");
   if (n > s->count) return fail(MLS_E_STASH, "n_microbatches exceeds the stashed micro-batches");
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
@@ -439,7 +451,7 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
     }
     const int m = (int)az.size();
     if (int rc = wgrad(s, az.data(), bdy.data(), m, g + s->off_wd, f, h, s->ld_f, s->ld_h)) return rc;
-    if (int rc = wgrad(s, ab.data(), bdgu.data(), m, g + s->off_wgu, h, 2 * f, s->ld_h, s->ld_gu)) return rc;
+    if (int rc = wgrad(s, ab.data(), bdgu.data(), m, g + s->off_wgu, h, 2 * f, s->ld_h, s->ld_gu, s->fuse_gu ? f : 0)) return rc;
     if (int rc = wgrad(s, ao.data(), bdh.data(), m, g + s->off_wo, s->qd, h, s->ld_qd, s->ld_h)) return rc;
     if (int rc = wgrad(s, aa.data(), bdqkv.data(), m, g + s->off_wqkv, h, s->qkvw, s->ld_h, s->ld_qkv)) return rc;
   }
@@ -481,9 +493,13 @@ int mls_stage_get_params(mls_stage* s, void* dst) {
   PTensor t[6];
   param_tensors(s, t);
   for (int l = 0; l < s->c.max_layers; l++)
-    for (auto& e : t)
-      HIP_TRY(copy2d(s, (char*)dst + (size_t(l) * s->layer_params + e.off) * s->es, e.cols, s->param(l, e.ioff), e.ld,
-                     e.rows, e.cols));
+    for (auto& e : t) {
+      char* d = (char*)dst + (size_t(l) * s->layer_params + e.off) * s->es;
+      if (e.tid == MLS_P_WGU && s->fuse_gu)
+        HIP_TRY(mls::gu_permute(s->param(l, e.ioff), e.ld, d, e.cols, e.rows, s->c.ffn, false, s->st));
+      else
+        HIP_TRY(copy2d(s, d, e.cols, s->param(l, e.ioff), e.ld, e.rows, e.cols));
+    }
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
@@ -493,9 +509,13 @@ int mls_stage_set_params(mls_stage* s, const void* src) {
   PTensor t[6];
   param_tensors(s, t);
   for (int l = 0; l < s->c.max_layers; l++)
-    for (auto& e : t)
-      HIP_TRY(copy2d(s, s->param(l, e.ioff), e.ld, (const char*)src + (size_t(l) * s->layer_params + e.off) * s->es,
-                     e.cols, e.rows, e.cols));
+    for (auto& e : t) {
+      const char* p = (const char*)src + (size_t(l) * s->layer_params + e.off) * s->es;
+      if (e.tid == MLS_P_WGU && s->fuse_gu)
+        HIP_TRY(mls::gu_permute(p, e.cols, s->param(l, e.ioff), e.ld, e.rows, s->c.ffn, true, s->st));
+      else
+        HIP_TRY(copy2d(s, s->param(l, e.ioff), e.ld, p, e.cols, e.rows, e.cols));
+    }
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
@@ -546,7 +566,10 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
       default: return fail(MLS_E_RANGE, "unknown tensor id");
     }
   }
-  HIP_TRY(copy2d(s, dst, cols, src, ld, T, cols));  // dst is dense
+  if ((id == MLS_T_GU || id == MLS_T_DGU) && s->fuse_gu)  // dst is dense and in the public column order
+    HIP_TRY(mls::gu_permute(src, ld, dst, cols, T, s->c.ffn, false, s->st));
+  else
+    HIP_TRY(copy2d(s, dst, cols, src, ld, T, cols));
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
@@ -583,6 +606,8 @@ int mls_gemm(int32_t dtype, int32_t mode, const void* A, int64_t lda, const void
   if (M < 0 || N < 0 || K < 0 || M % 8 || N % 8 || K % 8 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
     return fail(MLS_E_CONFIG, "mls_gemm: dimensions must be non-negative multiples of 8 below 2^24");
   const int64_t a_len = mode == mls::GEMM_TN ? M : K, b_len = mode == mls::GEMM_NT ? K : N;
+  if ((uintptr_t(A) | uintptr_t(B) | uintptr_t(C) | uintptr_t(R)) & 15)
+    return fail(MLS_E_CONFIG, "mls_gemm: operands must be 16-byte aligned");
   if (lda == 0) lda = a_len;
   if (ldb == 0) ldb = b_len;
   if (ldc == 0) ldc = N;

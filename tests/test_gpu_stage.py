@@ -17,6 +17,9 @@ TINY = synth.CONFIGS["tiny"]
 # grouped KV heads, ragged everything: seq not a multiple of any tile, ffn = 8*41, 3 layers, 3 micro-batches
 RAGGED = synth.StageShape(hidden=192, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=328, seq=200, micro_batch=2,
                           layers=3, microbatches=3)
+# ffn a multiple of 32 (SwiGLU runs fused into the contractions around it), 2 ffn = 704 not a multiple of any tile
+FUSED_RAGGED = synth.StageShape(hidden=192, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=352, seq=200, micro_batch=2,
+                                layers=3, microbatches=3)
 GQA128 = synth.StageShape(hidden=256, n_q_heads=4, n_kv_heads=1, head_dim=128, ffn=512, seq=328, micro_batch=1,
                           layers=1, microbatches=2)
 
@@ -65,6 +68,23 @@ def test_tiny_bf16_matches_oracle_1e2():
 def test_ragged_gqa_fp32_and_bf16_multi_microbatch():
     _check(RAGGED.with_(dtype="fp32"), [3, 3, 3], 1e-4)
     _check(RAGGED, [3, 3, 3], 1e-2)
+
+
+def test_ragged_shape_with_fused_swiglu():
+    """ffn % 32 == 0 switches w_gu, gu and dgu to the interleaved gate/up column order inside the library; weights
+    (generator and get/set), the captured gu / dgu operands and the w_gu gradient must still come out in the
+    public order."""
+    import paper_2410_13333_amd as mls
+    sh = FUSED_RAGGED
+    st = mls.Stage.from_shape(sh, seed=1000)
+    bits, _ = synth.make_params(sh, 1000)
+    assert np.array_equal(storage_bits(st.get_params()), bits)
+    p = st.get_params()
+    st.set_params(p.flip(0).contiguous())
+    assert np.array_equal(storage_bits(st.get_params()), bits[::-1])
+    st.close()
+    _check(sh, [3, 3, 3], 1e-2)
+    _check(sh, [1, 3, 2], 1e-2, interleave=True)
 
 
 def test_head_dim_128_gqa_single_kv_head():
@@ -154,12 +174,13 @@ def test_zero_layers_zero_microbatches_and_errors():
     assert e.value.code == -1
 
 
-def test_weight_gradient_contraction_given_identical_operands_1e4():
+@pytest.mark.parametrize("base", ["ragged", "fused"])
+def test_weight_gradient_contraction_given_identical_operands_1e4(base):
     """The 1e-4 bar of the fp32-accumulated weight gradients: capture the bf16 operand pairs of every
     weight-gradient contraction of layer 0 and rebuild sum_mb X^T dY in fp64 from exactly those operands."""
     import torch
     import paper_2410_13333_amd as mls
-    sh = RAGGED.with_(layers=1)
+    sh = (RAGGED if base == "ragged" else FUSED_RAGGED).with_(layers=1)
     n = 3
     st = mls.Stage.from_shape(sh, seed=1000, max_inflight=1)
     g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
