@@ -101,6 +101,15 @@ def run_plan_sweep(plans, steps):
            "max_relative_residual": float(resid.max()),
            "r2": float(1 - np.sum((t - fit) ** 2) / np.sum((t - t.mean()) ** 2)),
            "plans": [{"layers": k, "microbatches": m, "ms": float(ms)} for (k, m), ms in zip(plans, times)]}
+    # Close the loop of Sec. 4.2: the measured tau(b) feeds the planner's lower level.  Orchestration of the paper's
+    # 110B case study (Sec. 7.3, Table 4: 80 layers, 64 micro-batches, two pipelines of 8 and 6 stages), group rates
+    # taken as inversely proportional to the group size (1, 2, 4 or 8 GPUs).
+    import timeit
+    pipes = [[1.0, 1.0, 1.0, 0.25, 0.25, 0.25, 0.125, 0.125], [0.5, 0.5, 0.5, 0.125, 0.125, 0.125]]
+    ls, ms, est = mls.plan_lower_level(pipes, 80, 64, float(c))
+    solve_us = min(timeit.repeat(lambda: mls.plan_lower_level(pipes, 80, 64, float(c)), number=200, repeat=3)) / 200 * 1e6
+    out["plan_example"] = {"pipelines": pipes, "layers": ls, "microbatches": ms, "estimated_step_ms": est,
+                           "solve_us_incl_binding": solve_us}
     st.close()
     return out
 

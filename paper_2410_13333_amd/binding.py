@@ -58,6 +58,14 @@ def lib():
         L.mls_stage_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.mls_gemm.argtypes = [i32, i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, vp]
         L.mls_last_error.restype = C.c_char_p
+        dp_, ip_ = C.POINTER(C.c_double), C.POINTER(i64)
+        L.mls_plan_layers.argtypes = [dp_, ip_, i32, i64, ip_, dp_]
+        L.mls_plan_microbatches.argtypes = [dp_, i32, i64, ip_, dp_]
+        L.mls_plan_lower_level.argtypes = [dp_, ip_, C.POINTER(i32), i32, i64, i64, C.c_double, ip_, ip_, dp_]
+        L.mls_grouping_time_ratio.argtypes = [dp_, i32, dp_, i32]
+        L.mls_grouping_time_ratio.restype = C.c_double
+        L.mls_theoretic_slowdown.argtypes = [i64, dp_, i32]
+        L.mls_theoretic_slowdown.restype = C.c_double
         _lib = L
     return _lib
 
@@ -185,3 +193,57 @@ def gemm(mode, a, b, c, r=None, stream=None):
     st = stream if stream is not None else torch.cuda.current_stream()
     _check(lib().mls_gemm(dtype, mode, _ptr(a), a.stride(0), _ptr(b), b.stride(0), _ptr(c), c.stride(0), _ptr(r),
                           M, N, K, C.c_void_p(st.cuda_stream)))
+
+
+# ---- include/mls_plan.h: the planner's lower level (host arrays in, host arrays out)
+def _darr(v):
+    return (C.c_double * len(v))(*[float(x) for x in v])
+
+
+def _caps(cap, n):
+    if cap is None:
+        return None
+    assert len(cap) == n
+    return (C.c_int64 * n)(*[-1 if c is None else int(c) for c in cap])
+
+
+def plan_layers(y, L, cap=None):
+    """Eq. 2: returns (layers per stage, optimal bottleneck max_j y_j l_j)."""
+    n = len(y)
+    out, o = (C.c_int64 * n)(), C.c_double()
+    _check(lib().mls_plan_layers(_darr(y), _caps(cap, n), n, int(L), out, C.byref(o)))
+    return list(out), o.value
+
+
+def plan_microbatches(o, n_mb):
+    """Eq. 3: returns (micro-batches per pipeline, optimal max_i o_i m_i)."""
+    n = len(o)
+    out, t = (C.c_int64 * n)(), C.c_double()
+    _check(lib().mls_plan_microbatches(_darr(o), n, int(n_mb), out, C.byref(t)))
+    return list(out), t.value
+
+
+def plan_lower_level(pipelines, L, n_mb, tau, caps=None):
+    """Eq. 1 for fixed pipelines (list of lists of stage rates): returns (layers per pipeline per stage,
+    micro-batches per pipeline, estimated step time)."""
+    pp = [len(p) for p in pipelines]
+    flat = [y for p in pipelines for y in p]
+    fcap = None if caps is None else [c for p in caps for c in p]
+    l, m, t = (C.c_int64 * len(flat))(), (C.c_int64 * len(pp))(), C.c_double()
+    _check(lib().mls_plan_lower_level(_darr(flat), _caps(fcap, len(flat)), (C.c_int32 * len(pp))(*pp), len(pp), int(L),
+                                      int(n_mb), float(tau), l, m, C.byref(t)))
+    ls, at = [], 0
+    for k in pp:
+        ls.append(list(l[at:at + k]))
+        at += k
+    return ls, list(m), t.value
+
+
+def grouping_time_ratio(y1, y2):
+    """Theorem 2: T'/T'' of two groupings under the relaxed problem."""
+    return lib().mls_grouping_time_ratio(_darr(y1), len(y1), _darr(y2), len(y2))
+
+
+def theoretic_slowdown(n_gpus, x):
+    """Sec. 7.2: best possible step-time ratio with stragglers of rates x among n_gpus GPUs."""
+    return lib().mls_theoretic_slowdown(int(n_gpus), _darr(x) if len(x) else None, len(x))

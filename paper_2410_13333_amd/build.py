@@ -12,13 +12,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmls.so")
-SOURCES = ["stage.hip", "gemm_bf16.hip", "gemm_bf16_dma.hip", "gemm_f32.hip", "attention_bf16.hip", "attention_f32.hip", "elementwise.hip"]
+SOURCES = ["stage.hip", "gemm_bf16.hip", "gemm_bf16_dma.hip", "gemm_f32.hip", "attention_bf16.hip", "attention_f32.hip", "elementwise.hip", "plan.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
 def _compile(src):
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"

@@ -9,6 +9,9 @@ namespace mls {
 enum { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
 enum { DT_BF16 = 0, DT_FP32 = 1 };
 
+// records `msg` as the calling thread's mls_last_error text and returns `code` (stage.hip)
+int set_error(int code, const char* msg);
+
 // ---- contractions (gemm_bf16.hip, gemm_f32.hip); modes as documented at mls_gemm; leading dims in elements
 // (ldr: row stride of the residual R, ignored when R is null)
 hipError_t gemm_bf16(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,

@@ -22,6 +22,11 @@ int fail(int code, const std::string& msg) {
 int fail_hip(hipError_t e, const char* what) {
   return fail(e == hipErrorOutOfMemory ? MLS_E_NOMEM : MLS_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
+}  // namespace
+namespace mls {
+int set_error(int code, const char* msg) { return fail(code, msg); }
+}  // namespace mls
+namespace {
 #define HIP_TRY(expr)                                   \
   do {                                                  \
     hipError_t e_ = (expr);                             \
