@@ -44,18 +44,23 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ o, int64_t ldo,
                                                          const T* __restrict__ d_o, int64_t ldd,
                                                          float* __restrict__ delta, int b, int S, int nq, int d) {
-  // one wavefront per (token, head)
-  const int64_t w = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 6;
-  const int lane = threadIdx.x & 63;
-  if (w >= int64_t(b) * S * nq) return;
-  const int hq = int(w % nq);
-  const int64_t t = w / nq;
-  const T* po = o + t * ldo + hq * d;
-  const T* pd = d_o + t * ldd + hq * d;
+  // 16 lanes per (token, head) row of d <= 128 elements, 8 elements per lane: four rows per wavefront
+  const int64_t w = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 4;
+  const int c = (threadIdx.x & 15) * 8;
+  const bool live = w < int64_t(b) * S * nq;
+  const int hq = live ? int(w % nq) : 0;
+  const int64_t t = live ? w / nq : 0;
   float s = 0.f;
-  for (int c = lane; c < d; c += 64) s += to_f32(po[c]) * to_f32(pd[c]);
-  s = wave_sum(s);
-  if (lane == 0) delta[(int64_t(t / S) * nq + hq) * S + (t % S)] = s;
+  if (live && c < d) {
+    float a[8], g[8];
+    load8(o + t * ldo + hq * d + c, a);
+    load8(d_o + t * ldd + hq * d + c, g);
+#pragma unroll
+    for (int e = 0; e < 8; e++) s += a[e] * g[e];
+  }
+#pragma unroll
+  for (int m = 8; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+  if (live && c == 0) delta[(int64_t(t / S) * nq + hq) * S + (t % S)] = s;
 }
 
 __global__ __launch_bounds__(64) void attn_dq_f32_kernel(const float* __restrict__ qkv, int64_t ld,
@@ -133,7 +138,7 @@ hipError_t attn_delta(int dt, const void* o, int64_t ld_o, const void* d_o, int6
                       int nq, int d, hipStream_t st) {
   const int64_t waves = int64_t(b) * S * nq;
   if (waves == 0) return hipSuccess;
-  const int blocks = int((waves * 64 + 255) / 256);
+  const int blocks = int((waves * 16 + 255) / 256);  // 16 lanes per row
   if (dt == DT_BF16)
     hipLaunchKernelGGL(attn_delta_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)o, ld_o,
                        (const bf16_t*)d_o, ld_do, delta, b, S, nq, d);

@@ -86,15 +86,20 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
         }
       }
     }
+    float res[NORM_MAXC][8];  // requested before the reduction so that their latency overlaps it
+#pragma unroll
+    for (int i = 0; i < NORM_MAXC; i++) {
+      const int c = threadIdx.x + i * EW_THREADS;
+      if (c < nchunk) load8(dres + row * ld_dres + c * 8, res[i]);
+    }
     const float mean = block_sum(dot, red) / (float)h;
 #pragma unroll
     for (int i = 0; i < NORM_MAXC; i++) {
       const int c = threadIdx.x + i * EW_THREADS;
       if (c < nchunk) {
-        float res[8], o[8];
-        load8(dres + row * ld_dres + c * 8, res);
+        float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = res[e] + r * (dn[i][e] - n[i][e] * mean);
+        for (int e = 0; e < 8; e++) o[e] = res[i][e] + r * (dn[i][e] - n[i][e] * mean);
         store8(dx + row * ld_dx + c * 8, o);
       }
     }
