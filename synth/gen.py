@@ -223,3 +223,85 @@ def plan_sweep(seed=4000, n_plans=16, layer_range=(2, 9), mb_range=(1, 16)):
         m = mb_range[0] + uniform_u64(seed, TID_PLAN, 0, 2 * i + 1) % (mb_range[1] - mb_range[0] + 1)
         plans.append((int(k), int(m)))
     return plans
+
+
+# ---------------------------------------------------------------- first / last stage (embedding, final norm, LM head)
+TID_EMBED, TID_GAMMA_F, TID_WLM = 6, 7, 8
+TID_TOKENS, TID_TARGETS = 19, 20
+
+
+@dataclass(frozen=True)
+class EndsShape:
+    """Shape of the non-uniform layers of the first and last pipeline stage (Appendix B.4): token embedding, final
+    RMSNorm, LM head, mean cross-entropy loss.  LLaMA-2 (Sec. 7.1) has a vocabulary of 32000."""
+    hidden: int
+    vocab: int
+    seq: int
+    micro_batch: int
+    microbatches: int
+    rms_eps: float = 1e-5
+    dtype: str = "bf16"
+
+    @property
+    def tokens(self): return self.seq * self.micro_batch
+    def with_(self, **kw): return replace(self, **kw)
+
+    def model_flops_mb(self):
+        """fwd+bwd model FLOPs of the LM head on one micro-batch (the embedding and the loss are not contractions)."""
+        return 3 * 2 * self.tokens * self.hidden * self.vocab
+
+
+ENDS_CONFIGS = {
+    "tiny": EndsShape(256, 1000, 128, 2, 2),
+    "7b": EndsShape(4096, 32000, 4096, 1, 4),
+}
+
+
+def ends_param_layout(sh: EndsShape):
+    """(name, tensor_id, rows, cols, offset) of embed [V, h], gamma_f [h], w_lm [h, V]."""
+    items = [("embed", TID_EMBED, sh.vocab, sh.hidden), ("gamma_f", TID_GAMMA_F, 1, sh.hidden),
+             ("w_lm", TID_WLM, sh.hidden, sh.vocab)]
+    out, off = [], 0
+    for name, tid, r, c in items:
+        out.append((name, tid, r, c, off))
+        off += r * c
+    return out
+
+
+def make_ends_params(sh: EndsShape, seed):
+    """Flat parameter vector (storage array, fp64 values) of the first/last-stage layers."""
+    lay = ends_param_layout(sh)
+    total = lay[-1][4] + lay[-1][2] * lay[-1][3]
+    vals = np.empty(total, dtype=np.float64)
+    for name, tid, r, c, off in lay:
+        z = normal(seed, tid, 0, r * c)
+        vals[off:off + r * c] = (1.0 + 0.02 * z) if name.startswith("gamma") else 0.02 * z
+    return round_to_storage(vals, sh.dtype)
+
+
+def split_ends_params(sh: EndsShape, flat64):
+    d = {}
+    for name, tid, r, c, off in ends_param_layout(sh):
+        v = flat64[off:off + r * c]
+        d[name] = v.reshape(c) if r == 1 else v.reshape(r, c)
+    return d
+
+
+def _token_draws(seed, tid, mb, n, vocab):
+    s = _stream(seed, tid, mb)
+    with np.errstate(over="ignore"):
+        r = mix64(s + np.uint64(2) * np.arange(n, dtype=np.uint64))
+    return (r % np.uint64(vocab)).astype(np.int32)
+
+
+def make_tokens(sh: EndsShape, seed, mb, skew=False):
+    """Token ids [b, S] of micro-batch mb, uniform over the vocabulary; skew=True folds them onto a 64th of it so
+    that many positions share a token (the embedding gradient then sums several rows per table row)."""
+    t = _token_draws(seed, TID_TOKENS, mb, sh.tokens, sh.vocab)
+    if skew:
+        t = t % np.int32(max(1, sh.vocab // 64))
+    return t.reshape(sh.micro_batch, sh.seq)
+
+
+def make_targets(sh: EndsShape, seed, mb):
+    return _token_draws(seed, TID_TARGETS, mb, sh.tokens, sh.vocab).reshape(sh.micro_batch, sh.seq)
