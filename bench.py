@@ -114,12 +114,59 @@ def run_plan_sweep(plans, steps):
     return out
 
 
+def run_ends(steps, warmup, n_mb=4):
+    """The non-uniform layers of the first and last stage at the 7B shape (hidden 4096, vocabulary 32000, 4096 tokens
+    per micro-batch): embedding forward, head forward (final RMSNorm, LM head, cross-entropy), head backward and
+    embedding backward over n_mb micro-batches per step.  Not the headline metric: reported beside it."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2410_13333_amd as mls
+    sh = synth.ENDS_CONFIGS["7b"].with_(microbatches=n_mb)
+    en = mls.Ends.from_shape(sh, seed=1101, max_inflight=n_mb)
+    toks = [torch.from_numpy(synth.make_tokens(sh, 2100, mb).reshape(-1)).cuda() for mb in range(n_mb)]
+    tgts = [torch.from_numpy(synth.make_targets(sh, 2200, mb).reshape(-1)).cuda() for mb in range(n_mb)]
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    xs = [torch.empty(shape, dtype=en.tdtype, device="cuda") for _ in range(n_mb)]
+    ys = [torch.randn(shape, device="cuda").to(en.tdtype) for _ in range(n_mb)]
+    dy = torch.empty((n_mb,) + shape, dtype=en.tdtype, device="cuda")
+    dx = torch.randn((n_mb,) + shape, device="cuda").to(en.tdtype)
+    loss = torch.zeros(n_mb, dtype=torch.float32, device="cuda")
+    grads = torch.zeros(en.grad_elems, dtype=torch.float32, device="cuda")
+
+    def step():
+        grads.zero_()
+        for mb in range(n_mb):
+            en.embed_forward(toks[mb], xs[mb])
+        for mb in range(n_mb):
+            en.head_forward(ys[mb], tgts[mb], 1.0 / n_mb, loss[mb:mb + 1])
+        en.head_backward(grads, n_mb, dy)
+        en.embed_backward(dx, grads, n_mb)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flops = sh.model_flops_mb() * n_mb
+    out = {"metric": "first/last-stage layers fwd+bwd TFLOP/s (bf16)", "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"embedding + final RMSNorm + LM head + cross-entropy, hidden 4096, vocabulary 32000, "
+                                  f"{n_mb} micro-batches of 4096 tokens"},
+           "ms_per_microbatch": ms / n_mb, "mean_loss": float(loss.mean())}
+    en.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check)")
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -127,6 +174,9 @@ def main():
 
     if a.workload == "sweep":
         return plan_sweep(a)
+    if a.workload == "ends":
+        print(json.dumps(run_ends(a.steps, a.warmup)))
+        return
 
     import torch
     import synth

@@ -25,6 +25,14 @@ class MlsConfig(C.Structure):
                 ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
 
 
+class MlsEndsConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("vocab", C.c_int32), ("seq", C.c_int32), ("micro_batch", C.c_int32),
+                ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+PE_NAMES = {"embed": 0, "gamma_f": 1, "w_lm": 2}
+
+
 def lib_path():
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmls.so")
 
@@ -58,6 +66,20 @@ def lib():
         L.mls_stage_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.mls_gemm.argtypes = [i32, i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, vp]
         L.mls_last_error.restype = C.c_char_p
+        L.mls_ends_init.argtypes = [C.POINTER(MlsEndsConfig), u64, vp, C.POINTER(vp)]
+        L.mls_ends_free.argtypes = [vp]
+        L.mls_ends_free.restype = None
+        L.mls_embed_forward.argtypes = [vp, vp, vp]
+        L.mls_embed_backward.argtypes = [vp, vp, vp, i32]
+        L.mls_head_forward.argtypes = [vp, vp, vp, C.c_float, vp]
+        L.mls_head_backward.argtypes = [vp, vp, i32, vp]
+        L.mls_ends_grad_elems.argtypes = [vp]
+        L.mls_ends_grad_elems.restype = sz
+        L.mls_ends_param_layout.argtypes = [vp, i32, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.mls_ends_get_params.argtypes = [vp, vp]
+        L.mls_ends_set_params.argtypes = [vp, vp]
+        L.mls_ends_inflight.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+        L.mls_ends_debug_dlogits.argtypes = [vp, i32, vp]
         dp_, ip_ = C.POINTER(C.c_double), C.POINTER(i64)
         L.mls_plan_layers.argtypes = [dp_, ip_, i32, i64, ip_, dp_]
         L.mls_plan_microbatches.argtypes = [dp_, i32, i64, ip_, dp_]
@@ -193,6 +215,81 @@ def gemm(mode, a, b, c, r=None, stream=None):
     st = stream if stream is not None else torch.cuda.current_stream()
     _check(lib().mls_gemm(dtype, mode, _ptr(a), a.stride(0), _ptr(b), b.stride(0), _ptr(c), c.stride(0), _ptr(r),
                           M, N, K, C.c_void_p(st.cuda_stream)))
+
+
+# ---- include/mls_ends.h: the non-uniform layers of the first and the last pipeline stage
+class Ends:
+    """Token embedding (first stage) and final norm + LM head + loss (last stage); tensors are torch CUDA tensors."""
+
+    def __init__(self, hidden, vocab, seq, micro_batch, max_inflight, rms_eps=1e-5, dtype="bf16", seed=0, stream=None):
+        import torch
+        self.cfg = MlsEndsConfig(hidden, vocab, seq, micro_batch, max_inflight, rms_eps,
+                                 MLS_BF16 if dtype == "bf16" else MLS_FP32)
+        self.dtype = self.cfg.dtype
+        self.tdtype = _torch_dtype(self.dtype)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self._h = C.c_void_p(0)
+        _check(lib().mls_ends_init(C.byref(self.cfg), seed, C.c_void_p(self.stream.cuda_stream), C.byref(self._h)))
+
+    @classmethod
+    def from_shape(cls, sh, seed=0, max_inflight=None, stream=None):
+        return cls(sh.hidden, sh.vocab, sh.seq, sh.micro_batch, sh.microbatches if max_inflight is None else max_inflight,
+                   sh.rms_eps, sh.dtype, seed, stream)
+
+    def embed_forward(self, tokens, x):
+        _check(lib().mls_embed_forward(self._h, _ptr(tokens), _ptr(x)))
+
+    def embed_backward(self, dx, grads, n):
+        _check(lib().mls_embed_backward(self._h, _ptr(dx), _ptr(grads), n))
+
+    def head_forward(self, y, targets, loss_weight, loss):
+        _check(lib().mls_head_forward(self._h, _ptr(y), _ptr(targets), loss_weight, _ptr(loss)))
+
+    def head_backward(self, grads, n, dy):
+        _check(lib().mls_head_backward(self._h, _ptr(grads), n, _ptr(dy)))
+
+    @property
+    def grad_elems(self):
+        return lib().mls_ends_grad_elems(self._h)
+
+    @property
+    def inflight(self):
+        a, b = C.c_int32(), C.c_int32()
+        _check(lib().mls_ends_inflight(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def param_layout(self, which):
+        off, r, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(lib().mls_ends_param_layout(self._h, PE_NAMES[which] if isinstance(which, str) else which, C.byref(off),
+                                           C.byref(r), C.byref(c)))
+        return off.value, r.value, c.value
+
+    def get_params(self):
+        import torch
+        out = torch.empty(self.grad_elems, dtype=self.tdtype, device="cuda")
+        _check(lib().mls_ends_get_params(self._h, _ptr(out)))
+        return out
+
+    def set_params(self, src):
+        assert src.is_cuda and src.dtype == self.tdtype and src.numel() == self.grad_elems and src.is_contiguous()
+        _check(lib().mls_ends_set_params(self._h, _ptr(src)))
+
+    def debug_dlogits(self, slot=0):
+        import torch
+        out = torch.empty((self.cfg.seq * self.cfg.micro_batch, self.cfg.vocab), dtype=self.tdtype, device="cuda")
+        _check(lib().mls_ends_debug_dlogits(self._h, slot, _ptr(out)))
+        return out
+
+    def close(self):
+        if self._h:
+            lib().mls_ends_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # ---- include/mls_plan.h: the planner's lower level (host arrays in, host arrays out)

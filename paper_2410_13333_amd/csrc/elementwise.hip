@@ -90,7 +90,14 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
 #pragma unroll
     for (int i = 0; i < NORM_MAXC; i++) {
       const int c = threadIdx.x + i * EW_THREADS;
-      if (c < nchunk) load8(dres + row * ld_dres + c * 8, res[i]);
+      if (c < nchunk) {
+        if (dres) {
+          load8(dres + row * ld_dres + c * 8, res[i]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; e++) res[i][e] = 0.f;
+        }
+      }
     }
     const float mean = block_sum(dot, red) / (float)h;
 #pragma unroll

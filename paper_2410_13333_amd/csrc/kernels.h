@@ -42,7 +42,7 @@ hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void*
 hipError_t rmsnorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, void* a, int64_t lda, float* r, int T,
                        int h, float eps, hipStream_t st);
 // dx = dres + r*(dn - n*mean(dn*n)), dn = da*gamma, n = x*r;  dgamma += sum_t da*n (two-stage, deterministic).
-// partial: workspace of rmsnorm_bwd_blocks(T) * h floats.
+// partial: workspace of rmsnorm_bwd_blocks(T) * h floats.  dres may be null (no residual branch: dx without it).
 int rmsnorm_bwd_blocks(int T);
 hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
                        const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
