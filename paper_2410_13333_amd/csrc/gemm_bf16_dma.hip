@@ -64,11 +64,11 @@ struct SegArgs {
 };
 
 // ---- [row][k] tile: ROWS x BK elements, BK*2 bytes per row
-template <int ROWS, int BK>
+template <int ROWS, int BK, int NW = 4>
 struct RowTile {
   static constexpr int RB = BK * 2, CPR = RB / 16, RPB = 256 / RB;  // row bytes, chunks per row, rows per 256 B
   static constexpr int BYTES = ROWS * RB, RPI = 1024 / RB;          // rows per DMA instruction
-  static constexpr int NI = ROWS / RPI / 4;                         // DMA instructions per wave
+  static constexpr int NI = ROWS / RPI / NW;                        // DMA instructions per wave
   static_assert(RB == 64 || RB == 128, "BK must be 32 or 64");
   uint32_t goff[NI];  // byte offset of this lane's chunk at k-tile 0 (OOB if the row is out of range)
   int kcol[NI];       // its first k index inside a tile
@@ -94,11 +94,11 @@ struct RowTile {
 };
 
 // ---- [k][col] tile: BK x COLS elements, COLS*2 bytes per k-row
-template <int COLS, int BK>
+template <int COLS, int BK, int NW = 4>
 struct ColTile {
   static constexpr int CB = COLS * 2, CPR = CB / 16;
   static constexpr int BYTES = BK * CB, RPI = 1024 / CB;
-  static constexpr int NI = BK / RPI / 4;
+  static constexpr int NI = BK / RPI / NW;
   static_assert(CPR >= 16, "tile must be at least 128 columns wide");
   uint32_t goff[NI];  // byte offset at k-tile 0 (OOB if the column is out of range)
   __device__ __forceinline__ void init(int col0, int ncols, int64_t ld, int wave, int lane) {
@@ -127,19 +127,21 @@ struct ColTile {
   }
 };
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE, bool SEG>
-__global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE, bool SEG, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                        void* __restrict__ Cv, const bf16_t* __restrict__ R, int M,
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
                                                        int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m,
                                                        int col0, void* __restrict__ Xv, int64_t ldx, int xf,
                                                        SegArgs segs) {
-  using AT_R = RowTile<BM, BK>;
-  using AT_C = ColTile<BM, BK>;
-  using BT_R = RowTile<BN, BK>;
-  using BT_C = ColTile<BN, BK>;
+  using AT_R = RowTile<BM, BK, NW>;
+  using AT_C = ColTile<BM, BK, NW>;
+  using BT_R = RowTile<BN, BK, NW>;
+  using BT_C = ColTile<BN, BK, NW>;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-  constexpr int TM = BM / 64, TN = BN / 64, KS = BK / 16;
+  // NW wavefronts: 2 along M, NW/2 along N (4: one per SIMD, 128x128 each at 256x256; 8: two per SIMD, 128x64 each)
+  constexpr int WN = NW / 2;
+  constexpr int TM = BM / 64, TN = BN / WN / 32, KS = BK / 16;
   constexpr int LPT = (ATR ? AT_C::NI : AT_R::NI) + (BTR ? BT_C::NI : BT_R::NI);  // DMA loads per wave per tile
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   const int gsz = min(tiles_m - first_m, gm), in_grp = tile - grp * per_group;
   const int m0 = (first_m + in_grp % gsz) * BM, n0 = (in_grp / gsz) * BN;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
+  const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / WN);
 
   // prefetch cursor: the k-tile the next DMA instructions fetch (piece pf_seg, first row pf_k0)
   i32x4 ra = make_rsrc(SEG ? segs.a[0] : A, a_bytes), rb = make_rsrc(SEG ? segs.b[0] : B, b_bytes);
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   if (ATR) atc.init(m0, M, lda, wave, lane); else atr.init(m0, M, lda, wave, lane);
   if (BTR) btc.init(n0, N, ldb, wave, lane); else btr.init(n0, N, ldb, wave, lane);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS unsigned char*)smem;
-  const uint32_t a_wave = lds0 + wave * (A_BYTES / 4), b_wave = lds0 + A_BYTES + wave * (B_BYTES / 4);
+  const uint32_t a_wave = lds0 + wave * (A_BYTES / NW), b_wave = lds0 + A_BYTES + wave * (B_BYTES / NW);
   constexpr int NIA = ATR ? AT_C::NI : AT_R::NI;
   // DMA instruction d (0 .. LPT-1) of this wave for k-tile kt into `stage`: the first NIA belong to A
   // (`live` false: the tile does not exist; the load is sent out of range and only zero-fills a dead stage, which
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
     }
   };
   auto interleave_hint = [&]() {  // spread the LDS reads just issued over the first half of the MFMAs
-    if (NMFMA >= 16) {
+    if (NMFMA >= 8) {
 #pragma unroll
       for (int g = 0; g < NMFMA / 2; g++) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // 1 MFMA
@@ -300,8 +302,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   // access patterns spread over all banks.  `col0` is the column of the whole problem at which this launch's
   // column 0 sits (a launch may cover a column range).
   __syncthreads();  // every wave has read its last fragments and every DMA has landed
-  unsigned char* ws = smem + wave * 16384;
-  constexpr int CW = BN / 2;                          // columns of a wave tile
+  unsigned char* ws = smem + wave * (64 * 1024 / NW);
+  constexpr int CW = BN / WN;                         // columns of a wave tile
   constexpr int RB = CW * 2, NCH = RB / 16;           // bytes and 16-byte chunks per staged row (bf16)
   constexpr int RPI = 64 / NCH, NT = 32 / RPI;        // rows per whole-wave access, accesses per 32 rows
   const int crow = lane / NCH, cch = lane % NCH;      // this lane's row and chunk in a whole-wave access
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
       }
       // combine in the accumulator layout, in place
       constexpr int ZRB = CW, ZNCH = ZRB / 16;  // SwiGLU product: half as many columns, staged behind the 8 KiB
-      unsigned char* wz = ws + 8192;
+      unsigned char* wz = ws + 32 * RB;
 #pragma unroll
       for (int q = 0; q < TN * 4; q++) {
         const int j = q >> 2, g = q & 3;
@@ -398,12 +400,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const bf16_t* __restrict_
   }
 }
 
-template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE = PIPE_PLAIN, bool SEG = false>
+template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE = PIPE_PLAIN, bool SEG = false, int NW = 4>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                   int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
                   const SegArgs* segs = nullptr, int col0 = 0, void* X = nullptr, int64_t ldx = 0, int xf = 0) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
-  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG>;
+  auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;
   static bool attr_set = false;
@@ -413,7 +415,7 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
     attr_set = true;
   }
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(256), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm,
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(NW * 64), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm,
                      col0, X, ldx, xf, sa);
   return hipGetLastError();
 }
@@ -445,14 +447,20 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st,
                     const Extra& x = Extra()) {
   const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
-  // Measured on the 7B shapes: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
+  // Measured on the 7B stage: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
   // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.  Deeper pipelines
   // and a two-stage loop with its barrier ahead of the last substep all measured within noise of these or slower.
   constexpr int BK = BTR ? 32 : 64, NS = BTR ? 4 : 2, PIPE = BTR ? PIPE_SKEW : PIPE_PLAIN;
+  // Wavefronts per 256x256 workgroup, by measurement on the 7B stage: the bf16-epilogue modes run 8 (two per SIMD,
+  // 128x64 each: the second wavefront covers the first one's barrier and load waits; forward -5 %, data gradient
+  // -3 %), the fp32 read-modify-write mode runs 4 (128x128 each; 8 measured 2.5 % slower there).
+  constexpr bool nw8 = EPI != EPI_F32_ACC;
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
+      hipError_t e = nw8 ? launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, 8>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
+                                                                    nullptr, 0, x.X, x.ldx, x.xf)
+                         : launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
                                                                     nullptr, 0, x.X, x.ldx, x.xf);
       if (e != hipSuccess) return e;
       // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
@@ -461,6 +469,8 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
       return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st,
                                                             nullptr, n1, x.X, x.ldx, x.xf);
     }
+    if (nw8) return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, 8>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
+                                                          x.X, x.ldx, x.xf);
     return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
                                                           x.X, x.ldx, x.xf);
   }
