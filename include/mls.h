@@ -16,7 +16,8 @@
  * at init and returns without synchronising (exceptions: init, free, get/set params and debug reads, which
  * synchronise that stream).  The caller owns x, y, dY, dX and grads; the library owns weights, rotary
  * tables, the activation stash and its workspace, all allocated in mls_stage_init (the forward and
- * backward calls allocate nothing).
+ * backward calls allocate nothing).  x, y, dY, dX, grads and the operands of mls_gemm must be 16-byte aligned
+ * (MLS_E_CONFIG otherwise).
  *
  * Every function that returns int returns MLS_OK (0) or a negative MLS_E_* code; a message for the last
  * failure on the calling thread is available from mls_last_error().  No C++ exception crosses this ABI.
