@@ -161,12 +161,41 @@ def run_ends(steps, warmup, n_mb=4):
     return out
 
 
+def run_optim(steps, warmup):
+    """AdamW step on the parameters of the 7B-shaped 4-layer stage (809.5 M parameters, bf16 storage, fp32 master
+    weights and moments): one HBM-bound kernel, 30 B per parameter."""
+    import torch
+    import synth
+    import paper_2410_13333_amd as mls
+    sh = synth.CONFIGS["7b"]
+    n = sh.layers * synth.layer_param_elems(sh)
+    p = (0.02 * torch.randn(n, device="cuda")).to(torch.bfloat16)
+    g = torch.randn(n, device="cuda", dtype=torch.float32)
+    opt = mls.Optim(p)
+    for _ in range(warmup):
+        opt.step(g, p, lr=1e-4)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        opt.step(g, p, lr=1e-4)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    gbs = n * 30 / (ms * 1e-3) / 1e9
+    out = {"metric": "AdamW step GB/s", "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic", "config": {"workload": f"AdamW on {n} parameters (7B-shaped stage, 4 layers), bf16 storage"},
+           "roofline": {"bound": "hbm", "kernel": "adamw_kernel", "achieved": gbs, "peak": 8000.0, "unit": "GB/s",
+                        "frac": gbs / 8000.0, "traffic": None}}
+    opt.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers)")
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -176,6 +205,9 @@ def main():
         return plan_sweep(a)
     if a.workload == "ends":
         print(json.dumps(run_ends(a.steps, a.warmup)))
+        return
+    if a.workload == "optim":
+        print(json.dumps(run_optim(a.steps, a.warmup)))
         return
 
     import torch

@@ -2,6 +2,6 @@
 with a run-time layer count and micro-batch count.  Thin ctypes binding over libmls.so (include/mls.h)."""
 from .binding import (  # noqa: F401
     MlsError, MlsConfig, Stage, gemm, lib, lib_path, P_NAMES, T_IDS, MLS_BF16, MLS_FP32,
-    Ends, MlsEndsConfig, PE_NAMES,
+    Ends, MlsEndsConfig, PE_NAMES, Optim, Probe, MlsAdamW,
     plan_layers, plan_microbatches, plan_lower_level, grouping_time_ratio, theoretic_slowdown,
 )

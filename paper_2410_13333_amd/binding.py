@@ -30,6 +30,11 @@ class MlsEndsConfig(C.Structure):
                 ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
 
 
+class MlsAdamW(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
+
+
 PE_NAMES = {"embed": 0, "gamma_f": 1, "w_lm": 2}
 
 
@@ -81,6 +86,20 @@ def lib():
         L.mls_ends_inflight.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
         L.mls_ends_debug_dlogits.argtypes = [vp, i32, vp]
         dp_, ip_ = C.POINTER(C.c_double), C.POINTER(i64)
+        L.mls_optim_init.argtypes = [sz, vp, i32, vp, C.POINTER(vp)]
+        L.mls_optim_free.argtypes = [vp]
+        L.mls_optim_free.restype = None
+        L.mls_optim_step.argtypes = [vp, vp, C.POINTER(MlsAdamW), C.c_float, vp]
+        L.mls_optim_steps.argtypes = [vp]
+        L.mls_optim_steps.restype = i64
+        L.mls_optim_read.argtypes = [vp, i32, vp]
+        L.mls_probe_init.argtypes = [C.c_double, C.c_double, vp, C.POINTER(vp)]
+        L.mls_probe_free.argtypes = [vp]
+        L.mls_probe_free.restype = None
+        L.mls_probe_begin.argtypes = [vp]
+        L.mls_probe_end.argtypes = [vp, i32, i32]
+        L.mls_probe_read.argtypes = [vp, dp_, dp_, C.POINTER(i32)]
+        L.mls_probe_feed.argtypes = [vp, C.c_double, i32, i32, dp_, C.POINTER(i32)]
         L.mls_plan_layers.argtypes = [dp_, ip_, i32, i64, ip_, dp_]
         L.mls_plan_microbatches.argtypes = [dp_, i32, i64, ip_, dp_]
         L.mls_plan_lower_level.argtypes = [dp_, ip_, C.POINTER(i32), i32, i64, i64, C.c_double, ip_, ip_, dp_]
@@ -283,6 +302,80 @@ class Ends:
     def close(self):
         if self._h:
             lib().mls_ends_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- include/mls_optim.h: optimizer step and straggling-rate probe
+class Optim:
+    """AdamW on fp32 master weights for a flat parameter vector (a stage's or the first/last-stage layers')."""
+
+    def __init__(self, params, stream=None):
+        import torch
+        self.n = params.numel()
+        self.tdtype = params.dtype
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self._h = C.c_void_p(0)
+        _check(lib().mls_optim_init(self.n, _ptr(params), MLS_BF16 if params.dtype == torch.bfloat16 else MLS_FP32,
+                                    C.c_void_p(self.stream.cuda_stream), C.byref(self._h)))
+
+    def step(self, grads, params_out, lr, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, grad_scale=1.0):
+        hp = MlsAdamW(lr, beta1, beta2, eps, weight_decay)
+        _check(lib().mls_optim_step(self._h, _ptr(grads), C.byref(hp), grad_scale, _ptr(params_out)))
+
+    @property
+    def steps(self):
+        return lib().mls_optim_steps(self._h)
+
+    def read(self, which):
+        import torch
+        out = torch.empty(self.n, dtype=torch.float32, device="cuda")
+        _check(lib().mls_optim_read(self._h, {"w": 0, "m": 1, "v": 2}[which], _ptr(out)))
+        return out
+
+    def close(self):
+        if self._h:
+            lib().mls_optim_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Probe:
+    """Straggling-rate probe: brackets steps with HIP events (begin/end/read) or replays elapsed times (feed)."""
+
+    def __init__(self, tau_ref_ms, threshold=0.05, stream_handle=0):
+        self._h = C.c_void_p(0)
+        _check(lib().mls_probe_init(tau_ref_ms, threshold, C.c_void_p(stream_handle), C.byref(self._h)))
+
+    def begin(self):
+        _check(lib().mls_probe_begin(self._h))
+
+    def end(self, layers, microbatches):
+        _check(lib().mls_probe_end(self._h, layers, microbatches))
+
+    def read(self):
+        r, t, s = C.c_double(), C.c_double(), C.c_int32()
+        _check(lib().mls_probe_read(self._h, C.byref(r), C.byref(t), C.byref(s)))
+        return r.value, t.value, bool(s.value)
+
+    def feed(self, elapsed_ms, layers, microbatches):
+        r, s = C.c_double(), C.c_int32()
+        _check(lib().mls_probe_feed(self._h, elapsed_ms, layers, microbatches, C.byref(r), C.byref(s)))
+        return r.value, bool(s.value)
+
+    def close(self):
+        if self._h:
+            lib().mls_probe_free(self._h)
             self._h = C.c_void_p(0)
 
     def __del__(self):

@@ -10,13 +10,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     import paper_2410_13333_amd as mls
     headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
-    assert [os.path.basename(h) for h in headers] == ["mls.h", "mls_ends.h", "mls_plan.h"]
+    assert [os.path.basename(h) for h in headers] == ["mls.h", "mls_ends.h", "mls_optim.h", "mls_plan.h"]
     header = "".join(open(h).read() for h in headers)
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(mls_[a-z_]+)\s*\(", header))
     assert {"mls_stage_init", "mls_stage_forward", "mls_stage_backward", "mls_stage_free", "mls_plan_layers",
             "mls_plan_microbatches", "mls_plan_lower_level", "mls_embed_forward", "mls_embed_backward",
-            "mls_head_forward", "mls_head_backward"} <= names
+            "mls_head_forward", "mls_head_backward", "mls_optim_step", "mls_probe_read"} <= names
     lib = ctypes.CDLL(mls.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), n

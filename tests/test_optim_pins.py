@@ -54,3 +54,22 @@ def test_straggling_rate_rule():
     rates, shifts = oo.straggling_rates(elapsed, units, tau, 0.05)
     assert np.allclose(rates, x, rtol=1e-14)
     assert shifts == [False, False, True, False, False, True]
+
+
+def test_library_probe_replay_matches_the_rule():
+    """mls_probe_feed is host code: the same trace through the library (no GPU needed)."""
+    import paper_2410_13333_amd as mls
+    tau = 5.0
+    units = [(4, 4), (4, 4), (2, 8), (4, 4), (8, 1), (4, 4)]
+    x = [1.0, 1.02, 2.62, 2.62, 2.62 * 1.04, 1.0]
+    elapsed = [xi * tau * l * m for xi, (l, m) in zip(x, units)]
+    want_r, want_s = oo.straggling_rates(elapsed, [l * m for l, m in units], tau, 0.05)
+    pr = mls.Probe(tau, 0.05)
+    for e, (l, m), r, s in zip(elapsed, units, want_r, want_s):
+        got_r, got_s = pr.feed(e, l, m)
+        assert got_r == pytest.approx(r, rel=1e-14) and got_s == s
+    with pytest.raises(mls.MlsError):
+        pr.feed(1.0, 0, 4)
+    pr.close()
+    with pytest.raises(mls.MlsError):
+        mls.Probe(0.0)
