@@ -197,6 +197,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--recompute", action="store_true", help="activation recomputation: keep only the layer inputs")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -218,7 +219,7 @@ def main():
     sh = synth.CONFIGS[a.workload]
     K, M = sh.layers, sh.microbatches
     torch.cuda.set_device(0)
-    st = mls.Stage.from_shape(sh, seed=1001)
+    st = mls.Stage.from_shape(sh, seed=1001, recompute=a.recompute)
     shape = (sh.micro_batch, sh.seq, sh.hidden)
     xs = [to_device(synth.make_x(sh, 2001, mb)[0], sh.dtype) for mb in range(M)]
     dy = torch.stack([to_device(synth.make_dy(sh, 3001, mb)[0], sh.dtype) for mb in range(M)])
@@ -257,6 +258,8 @@ def main():
     gemm_n = sum(tm[k][1] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
     # algorithmic FLOPs of all GEMM launches of the timed steps / their summed duration; per launch = / launches
     gemm_flops = 3 * 2 * sh.tokens * sh.matrix_params() * K * M * a.steps
+    if a.recompute:  # the backward re-runs every forward contraction but the last one of the layer
+        gemm_flops += 2 * sh.tokens * (sh.matrix_params() - sh.ffn * sh.hidden) * K * M * a.steps
     gemm_flops_launch = gemm_flops / gemm_n
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -265,7 +268,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}-shaped stage: {K} layers x {M} micro-batches, hidden {sh.hidden}, "
                                f"{sh.n_q_heads}/{sh.n_kv_heads} heads x {sh.head_dim}, ffn {sh.ffn}, seq {sh.seq}, "
-                               f"micro-batch {sh.micro_batch}", "layers": K, "microbatches": M},
+                               f"micro-batch {sh.micro_batch}" + (", activation recomputation" if a.recompute else ""),
+                   "layers": K, "microbatches": M},
         "tokens_per_s": M * sh.tokens / (ms * 1e-3),
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "tau_ms_per_layer_microbatch": ms / (K * M),

@@ -91,6 +91,9 @@ typedef struct {
   float rms_eps;        /* added to the mean of squares inside the square root                       */
   float rope_base;      /* theta_i = rope_base^(-2i/head_dim), pairs (i, i + head_dim/2)             */
   int32_t dtype;        /* MLS_BF16 or MLS_FP32: storage type of activations and weights             */
+  int32_t recompute;    /* 1: activation recomputation -- keep only each layer's input and rebuild its   */
+                        /* other tensors in the backward (one more forward per layer, bit-identical      */
+                        /* results, 1/16 of the stash at the 7B shape); 0: keep everything               */
 } mls_config;
 
 /* Create a stage on the current HIP device.  Weights are drawn from the counter-based generator below
@@ -126,6 +129,23 @@ void mls_stage_free(mls_stage* s);
 /* Number of floats in `grads` (= number of parameters) for max_layers layers; 0 if s is NULL. */
 size_t mls_stage_grad_elems(const mls_stage* s);
 
+/* Device memory a stage of this configuration allocates in mls_stage_init, without creating one: the inputs of the
+ * linear memory model l*mu(b) + nu(b) <= C of the paper's cost model (Sec. 4.2; Appendix B.4).  In that model's
+ * terms, per layer: the forward activations of one kept micro-batch a_f = stash_bytes_per_layer_microbatch (the
+ * stash holds max_inflight of them: a stage j of a 1F1B pipeline with pp stages needs max_inflight = pp - j + 1),
+ * the model states s = param_bytes_per_layer + grad_bytes_per_layer (+ 12 B per parameter of optimizer state,
+ * mls_optim.h); workspace_bytes does not grow with the layer count. */
+typedef struct {
+  size_t total_bytes;                       /* = param_bytes + stash_bytes + workspace_bytes              */
+  size_t param_bytes;                       /* max_layers layers, storage type, internal row-padded layout */
+  size_t stash_bytes;                       /* max_inflight * max_layers entries                           */
+  size_t workspace_bytes;                   /* backward workspace, recomputation scratch, rotary tables    */
+  size_t param_bytes_per_layer;
+  size_t grad_bytes_per_layer;              /* fp32, the caller's buffer (not part of total_bytes)         */
+  size_t stash_bytes_per_layer_microbatch;
+} mls_memory;
+int mls_stage_memory(const mls_config* cfg, mls_memory* out);
+
 /* Offset (in elements, from the start of the flat parameter/grad vector), rows and cols of tensor `which`
  * (MLS_P_*) of `layer`; gains report rows = 1.  Errors: MLS_E_NULL, MLS_E_RANGE. */
 int mls_stage_param_layout(const mls_stage* s, int32_t layer, int32_t which, size_t* offset /*host*/,
@@ -143,7 +163,8 @@ int mls_stage_inflight(const mls_stage* s);
 int mls_stage_reset(mls_stage* s);
 
 /* Operand capture for tests: copy tensor `tensor_id` (MLS_T_*) of `layer` of the stash entry that is
- * `slot` pushes old (0 = oldest) into the DEVICE buffer dst, which must hold the tensor.  For MLS_T_D*
+ * `slot` pushes old (0 = oldest) into the DEVICE buffer dst, which must hold the tensor (with recomputation
+ * only MLS_T_X is kept: the other stash tensors give MLS_E_RANGE).  For MLS_T_D*
  * ids `layer` and `slot` are ignored.  Errors: MLS_E_NULL, MLS_E_RANGE, MLS_E_HIP. */
 int mls_stage_debug_read(mls_stage* s, int32_t tensor_id, int32_t layer, int32_t slot, void* dst);
 

@@ -44,6 +44,17 @@ int mls_plan_microbatches(const double* o, int32_t dp, int64_t n_mb, int64_t* m,
 int mls_plan_lower_level(const double* y, const int64_t* cap, const int32_t* pp, int32_t dp, int64_t L, int64_t n_mb,
                          double tau, int64_t* l, int64_t* m, double* step_time);
 
+/* Appendix B.4: the most layers stage j (1-based) of a 1F1B pipeline with pp stages can hold under the linear
+ * memory model l * mu + nu <= capacity - reserve, where the stage keeps the forward activations of pp - j earlier
+ * micro-batches beside the one in flight:  mu = a_f * (pp - j) + a_fb + s.
+ *   a_f   bytes of forward activations kept per layer for one micro-batch (of the micro-batch size in use)
+ *   a_fb  peak activation bytes per layer while one micro-batch runs forward and backward
+ *   s     bytes of parameters, gradients and optimizer states per layer
+ *   nu    bytes that do not grow with the layer count (workspace; first / last stage: the non-uniform layers)
+ * Returns floor((capacity - reserve - nu) / mu), at least 0; -1 on bad input (pp < 1, j outside [1, pp], mu <= 0). */
+int64_t mls_plan_layer_cap(double a_f, double a_fb, double s, double nu, int32_t pp, int32_t j, double capacity,
+                           double reserve);
+
 /* Theorem 2: T'/T'' of two groupings with group rates y1[n1] and y2[n2] under the relaxed problem (no memory
  * limit, real-valued assignments) = (sum 1/y2) / (sum 1/y1).  NaN on bad input. */
 double mls_grouping_time_ratio(const double* y1, int32_t n1, const double* y2, int32_t n2);

@@ -22,7 +22,14 @@ class MlsError(RuntimeError):
 class MlsConfig(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn", C.c_int32), ("seq", C.c_int32), ("micro_batch", C.c_int32), ("max_layers", C.c_int32),
-                ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
+                ("max_inflight", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
+                ("recompute", C.c_int32)]
+
+
+class MlsMemory(C.Structure):
+    _fields_ = [("total_bytes", C.c_size_t), ("param_bytes", C.c_size_t), ("stash_bytes", C.c_size_t),
+                ("workspace_bytes", C.c_size_t), ("param_bytes_per_layer", C.c_size_t),
+                ("grad_bytes_per_layer", C.c_size_t), ("stash_bytes_per_layer_microbatch", C.c_size_t)]
 
 
 class MlsEndsConfig(C.Structure):
@@ -69,6 +76,7 @@ def lib():
         L.mls_stage_debug_read.argtypes = [vp, i32, i32, i32, vp]
         L.mls_stage_timing.argtypes = [vp, i32]
         L.mls_stage_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+        L.mls_stage_memory.argtypes = [C.POINTER(MlsConfig), C.POINTER(MlsMemory)]
         L.mls_gemm.argtypes = [i32, i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, vp]
         L.mls_last_error.restype = C.c_char_p
         L.mls_ends_init.argtypes = [C.POINTER(MlsEndsConfig), u64, vp, C.POINTER(vp)]
@@ -103,6 +111,8 @@ def lib():
         L.mls_plan_layers.argtypes = [dp_, ip_, i32, i64, ip_, dp_]
         L.mls_plan_microbatches.argtypes = [dp_, i32, i64, ip_, dp_]
         L.mls_plan_lower_level.argtypes = [dp_, ip_, C.POINTER(i32), i32, i64, i64, C.c_double, ip_, ip_, dp_]
+        L.mls_plan_layer_cap.argtypes = [C.c_double] * 4 + [i32, i32, C.c_double, C.c_double]
+        L.mls_plan_layer_cap.restype = i64
         L.mls_grouping_time_ratio.argtypes = [dp_, i32, dp_, i32]
         L.mls_grouping_time_ratio.restype = C.c_double
         L.mls_theoretic_slowdown.argtypes = [i64, dp_, i32]
@@ -129,10 +139,10 @@ class Stage:
     """One GPU's pipeline stage.  Tensors are torch CUDA tensors used as plain device buffers."""
 
     def __init__(self, hidden, n_q_heads, n_kv_heads, head_dim, ffn, seq, micro_batch, max_layers, max_inflight,
-                 rms_eps=1e-5, rope_base=10000.0, dtype="bf16", seed=0, stream=None):
+                 rms_eps=1e-5, rope_base=10000.0, dtype="bf16", seed=0, stream=None, recompute=False):
         import torch
         self.cfg = MlsConfig(hidden, n_q_heads, n_kv_heads, head_dim, ffn, seq, micro_batch, max_layers, max_inflight,
-                             rms_eps, rope_base, MLS_BF16 if dtype == "bf16" else MLS_FP32)
+                             rms_eps, rope_base, MLS_BF16 if dtype == "bf16" else MLS_FP32, int(recompute))
         self.dtype = self.cfg.dtype
         self.tdtype = _torch_dtype(self.dtype)
         self.stream = stream if stream is not None else torch.cuda.current_stream()
@@ -140,12 +150,23 @@ class Stage:
         _check(lib().mls_stage_init(C.byref(self.cfg), seed, C.c_void_p(self.stream.cuda_stream), C.byref(self._h)))
 
     @classmethod
-    def from_shape(cls, sh, seed=0, max_layers=None, max_inflight=None, stream=None):
+    def from_shape(cls, sh, seed=0, max_layers=None, max_inflight=None, stream=None, recompute=False):
         """sh: any object with the StageShape fields (hidden, n_q_heads, ..., layers, microbatches, dtype)."""
         return cls(sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, sh.seq, sh.micro_batch,
                    sh.layers if max_layers is None else max_layers,
                    sh.microbatches if max_inflight is None else max_inflight,
-                   sh.rms_eps, sh.rope_base, sh.dtype, seed, stream)
+                   sh.rms_eps, sh.rope_base, sh.dtype, seed, stream, recompute)
+
+    @staticmethod
+    def memory(sh, max_layers=None, max_inflight=None, recompute=False):
+        """Device bytes a stage of this shape allocates (mls_stage_memory); no GPU needed."""
+        cfg = MlsConfig(sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, sh.seq, sh.micro_batch,
+                        sh.layers if max_layers is None else max_layers,
+                        sh.microbatches if max_inflight is None else max_inflight, sh.rms_eps, sh.rope_base,
+                        MLS_BF16 if sh.dtype == "bf16" else MLS_FP32, int(recompute))
+        m = MlsMemory()
+        _check(lib().mls_stage_memory(C.byref(cfg), C.byref(m)))
+        return {k: getattr(m, k) for k, _ in MlsMemory._fields_}
 
     # ---- hot path
     def forward(self, x, k_layers, y):
@@ -427,6 +448,11 @@ def plan_lower_level(pipelines, L, n_mb, tau, caps=None):
         ls.append(list(l[at:at + k]))
         at += k
     return ls, list(m), t.value
+
+
+def plan_layer_cap(a_f, a_fb, s, nu, pp, j, capacity, reserve=0.0):
+    """Appendix B.4: most layers stage j of pp can hold under the linear memory model."""
+    return lib().mls_plan_layer_cap(a_f, a_fb, s, nu, pp, j, capacity, reserve)
 
 
 def grouping_time_ratio(y1, y2):

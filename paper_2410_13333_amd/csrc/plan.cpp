@@ -130,6 +130,16 @@ int mls_plan_lower_level(const double* y, const int64_t* cap, const int32_t* pp,
   return MLS_OK;
 }
 
+int64_t mls_plan_layer_cap(double a_f, double a_fb, double s, double nu, int32_t pp, int32_t j, double capacity,
+                           double reserve) {
+  if (pp < 1 || j < 1 || j > pp || !(a_f >= 0) || !(a_fb >= 0) || !(s >= 0) || !(nu >= 0)) return -1;
+  const double mu = a_f * double(pp - j) + a_fb + s;
+  if (!(mu > 0) || !std::isfinite(mu)) return -1;
+  const double room = capacity - reserve - nu;
+  if (!(room > 0)) return 0;
+  return int64_t(std::floor(room / mu));
+}
+
 double mls_grouping_time_ratio(const double* y1, int32_t n1, const double* y2, int32_t n2) {
   if (!y1 || !y2 || n1 < 1 || n2 < 1 || !rates_ok(y1, n1) || !rates_ok(y2, n2)) return std::nan("");
   double s1 = 0, s2 = 0;

@@ -95,7 +95,11 @@ struct mls_stage {
   char* params = nullptr;  // storage type, internal layout
   float *cos_tab = nullptr, *sin_tab = nullptr;
   LayerStash ls;
-  char* stash = nullptr;  // [max_inflight][max_layers] LayerStash
+  // Stash entry of one (micro-batch, layer): the full LayerStash, or with activation recomputation only the
+  // layer input x (offset 0 in both).  rc_scratch: max_inflight full entries the recomputed tensors live in.
+  size_t entry_bytes = 0;
+  char* rc_scratch = nullptr;
+  char* stash = nullptr;  // [max_inflight][max_layers] entries
   std::vector<int> slot_k;
   int head = 0, count = 0;  // FIFO ring over the slots
   // backward workspace.  g0, g1 (ping-pong gradient of the residual stream), dgu, dh and dqkv exist once per
@@ -111,7 +115,7 @@ struct mls_stage {
   Timing tm;
 
   char* slot_layer(int slot, int layer) const {
-    return stash + (size_t(slot) * c.max_layers + layer) * ls.bytes;
+    return stash + (size_t(slot) * c.max_layers + layer) * entry_bytes;
   }
   char* param(int layer, size_t ioff) const { return params + (size_t(layer) * ilayer_params + ioff) * es; }
 };
@@ -146,6 +150,7 @@ int check_config(const mls_config& c) {
     return fail(MLS_E_CONFIG, "head_dim must be a multiple of 16 up to 128 for fp32 storage");
   if (c.seq < 1 || c.micro_batch < 1) return fail(MLS_E_CONFIG, "seq and micro_batch must be positive");
   if (c.max_layers < 0 || c.max_inflight < 1) return fail(MLS_E_CONFIG, "max_layers >= 0 and max_inflight >= 1 required");
+  if (c.recompute != 0 && c.recompute != 1) return fail(MLS_E_CONFIG, "recompute must be 0 or 1");
   if (!(c.rms_eps >= 0.f) || !(c.rope_base > 0.f)) return fail(MLS_E_CONFIG, "rms_eps >= 0 and rope_base > 0 required");
   const int64_t T = int64_t(c.seq) * c.micro_batch;
   const int64_t widest = std::max<int64_t>(2 * int64_t(c.ffn), int64_t(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim);
@@ -188,19 +193,21 @@ hipError_t copy2d(const mls_stage* s, void* dst, int64_t ld_dst, const void* src
 }
 
 // ---- one decoder layer, forward.  `x` lives in the stash entry already; `out` receives x + attention + MLP.
-int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
+// `x`: the layer input (row stride ld_h); `e`: the entry that receives the layer's other tensors (e + L.x itself
+// is not touched); out == nullptr skips the last contraction (recomputation needs only its operands).
+int layer_forward(mls_stage* s, int layer, const char* x, char* e, void* out, int64_t ld_out) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn;
   const int64_t lh = s->ld_h, lq = s->ld_qkv, lo = s->ld_qd, lg = s->ld_gu, lf = s->ld_f;
-  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.x, lh, s->param(layer, s->ioff_g1), e + L.a, lh, (float*)(e + L.r1), T, h,
+  LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, x, lh, s->param(layer, s->ioff_g1), e + L.a, lh, (float*)(e + L.r1), T, h,
                                     c.rms_eps, s->st));
   LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->ioff_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, lh, lq, lq));
   LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
                                      c.head_dim, lq, 1.f, s->st));
   LAUNCH(CLS_ATTN_FWD, mls::attn_fwd(s->dt, e + L.qkv, lq, e + L.o, lo, (float*)(e + L.lse), c.micro_batch, c.seq,
                                      c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->ioff_wo), e + L.h, e + L.x, T, h, s->qd, lo, lh, lh, lh));
+  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->ioff_wo), e + L.h, x, T, h, s->qd, lo, lh, lh, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, e + L.h, lh, s->param(layer, s->ioff_g2), e + L.b, lh, (float*)(e + L.r2), T, h,
                                     c.rms_eps, s->st));
   if (s->fuse_gu) {
@@ -210,7 +217,8 @@ int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
     LAUNCH(CLS_SWIGLU, mls::swiglu_fwd(s->dt, e + L.gu, lg, e + L.z, lf, T, f, s->st));
   }
   // `out` is either the next layer's x (row stride ld_h) or the caller's dense y
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->ioff_wd), out, e + L.h, T, h, f, lf, lh, ld_out, lh));
+  if (out)
+    LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.z, s->param(layer, s->ioff_wd), out, e + L.h, T, h, f, lf, lh, ld_out, lh));
   return MLS_OK;
 }
 
@@ -218,8 +226,8 @@ int layer_forward(mls_stage* s, int layer, char* e, void* out, int64_t ld_out) {
 // contractions, whose operands (dy, dgu, dh, dqkv of this micro-batch) stay in the workspace for them.
 // dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the gradient w.r.t. its input (row stride
 // ld_dx); g: this layer's slice of the caller's fp32 gradient vector (gains only here).
-int layer_backward_data(mls_stage* s, int layer, const char* e, int w, const void* dy, int64_t ld_dy, void* dx,
-                        int64_t ld_dx, float* g) {
+int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, int w, const void* dy, int64_t ld_dy,
+                        void* dx, int64_t ld_dx, float* g) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, wq = s->qkvw;
@@ -240,7 +248,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* e, int w, const voi
   LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
                                      c.head_dim, lq, -1.f, s->st));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
-  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
+  LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
                                     dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st));
   return MLS_OK;
 }
@@ -258,28 +266,8 @@ int wgrad(mls_stage* s, const void* const* A, const void* const* B, int n, float
   return MLS_OK;
 }
 
-void release(mls_stage* s) {
-  void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
-               s->delta, s->partial};
-  for (void* q : p)
-    if (q) (void)hipFree(q);
-  for (hipEvent_t e : s->tm.ev) (void)hipEventDestroy(e);
-  delete s;
-}
-
-}  // namespace
-
-extern "C" {
-
-const char* mls_last_error(void) { return g_err.c_str(); }
-
-int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_stage** out) {
-  if (!cfg || !out) return fail(MLS_E_NULL, "mls_stage_init: cfg and out must not be null");
-  *out = nullptr;
-  if (int rc = check_config(*cfg)) return rc;
-  mls_stage* s = new (std::nothrow) mls_stage();
-  if (!s) return fail(MLS_E_NOMEM, "host allocation failed");
-  s->c = *cfg;
+// every size and offset that follows from the configuration (no allocation)
+void layout(mls_stage* s) {
   const mls_config& c = s->c;
   s->dt = c.dtype == MLS_BF16 ? mls::DT_BF16 : mls::DT_FP32;
   s->es = c.dtype == MLS_BF16 ? 2 : 4;
@@ -287,7 +275,6 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   s->qd = c.n_q_heads * c.head_dim;
   s->kvd = c.n_kv_heads * c.head_dim;
   s->qkvw = s->qd + 2 * s->kvd;
-  s->st = (hipStream_t)hip_stream;
   const size_t h = c.hidden, f = c.ffn, T = s->T;
   s->off_g1 = 0;
   s->off_wqkv = h;
@@ -328,30 +315,68 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
   L.bytes = o;
   s->slot_k.assign(c.max_inflight, 0);
 
-  auto alloc = [&](void** p, size_t bytes) { return hipMalloc(p, bytes ? bytes : 256); };
-  const size_t nmb = c.max_inflight;
+  s->entry_bytes = c.recompute ? align256(T * s->ld_h * s->es) : L.bytes;
   s->mb_h = align256(T * s->ld_h * s->es);
   s->mb_gu = align256(T * s->ld_gu * s->es);
   s->mb_qkv = align256(T * s->ld_qkv * s->es);
-  hipError_t e = hipSuccess;
+}
+
+// the device allocations of a stage: name, bytes (what mls_stage_init allocates and mls_stage_memory reports)
+struct Alloc { void** p; size_t bytes; int kind; };  // kind: 0 parameters, 1 stash, 2 workspace
+std::vector<Alloc> allocations(mls_stage* s) {
+  const mls_config& c = s->c;
+  const size_t T = s->T, nmb = c.max_inflight, h = c.hidden;
   const int nb = mls::rmsnorm_bwd_blocks(s->T);
-  if ((e = alloc((void**)&s->params, size_t(c.max_layers) * s->ilayer_params * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
-      (e = alloc((void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4)) != hipSuccess ||
-      (e = alloc((void**)&s->stash, size_t(c.max_inflight) * c.max_layers * L.bytes)) != hipSuccess ||
-      (e = alloc((void**)&s->g0, nmb * s->mb_h)) != hipSuccess ||
-      (e = alloc((void**)&s->g1, nmb * s->mb_h)) != hipSuccess ||
-      (e = alloc((void**)&s->dz, T * s->ld_f * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dgu, nmb * s->mb_gu)) != hipSuccess ||
-      (e = alloc((void**)&s->dbuf, T * s->ld_h * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dh, nmb * s->mb_h)) != hipSuccess ||
-      (e = alloc((void**)&s->dc, T * s->ld_qd * s->es)) != hipSuccess ||
-      (e = alloc((void**)&s->dqkv, nmb * s->mb_qkv)) != hipSuccess ||
-      (e = alloc((void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4)) != hipSuccess ||
-      (e = alloc((void**)&s->partial, size_t(nb) * h * 4)) != hipSuccess) {
-    release(s);
-    return fail_hip(e, "hipMalloc");
-  }
+  return {
+      {(void**)&s->params, size_t(c.max_layers) * s->ilayer_params * s->es, 0},
+      {(void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4, 2},
+      {(void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4, 2},
+      {(void**)&s->stash, nmb * c.max_layers * s->entry_bytes, 1},
+      {(void**)&s->rc_scratch, c.recompute ? nmb * s->ls.bytes : 0, 2},
+      {(void**)&s->g0, nmb * s->mb_h, 2},
+      {(void**)&s->g1, nmb * s->mb_h, 2},
+      {(void**)&s->dz, T * s->ld_f * s->es, 2},
+      {(void**)&s->dgu, nmb * s->mb_gu, 2},
+      {(void**)&s->dbuf, T * s->ld_h * s->es, 2},
+      {(void**)&s->dh, nmb * s->mb_h, 2},
+      {(void**)&s->dc, T * s->ld_qd * s->es, 2},
+      {(void**)&s->dqkv, nmb * s->mb_qkv, 2},
+      {(void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4, 2},
+      {(void**)&s->partial, size_t(nb) * h * 4, 2},
+  };
+}
+
+void release(mls_stage* s) {
+  void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->rc_scratch, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
+               s->delta, s->partial};
+  for (void* q : p)
+    if (q) (void)hipFree(q);
+  for (hipEvent_t e : s->tm.ev) (void)hipEventDestroy(e);
+  delete s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mls_last_error(void) { return g_err.c_str(); }
+
+int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_stage** out) {
+  if (!cfg || !out) return fail(MLS_E_NULL, "mls_stage_init: cfg and out must not be null");
+  *out = nullptr;
+  if (int rc = check_config(*cfg)) return rc;
+  mls_stage* s = new (std::nothrow) mls_stage();
+  if (!s) return fail(MLS_E_NOMEM, "host allocation failed");
+  s->c = *cfg;
+  s->st = (hipStream_t)hip_stream;
+  layout(s);
+  const mls_config& c = s->c;
+  hipError_t e = hipSuccess;
+  for (const Alloc& al : allocations(s))
+    if (al.bytes && (e = hipMalloc(al.p, al.bytes)) != hipSuccess) {
+      release(s);
+      return fail_hip(e, "hipMalloc");
+    }
 
   // rotary table: angle(p, i) = p * base^(-2i/d), evaluated in fp64 on the host, stored as fp32
   {
@@ -396,7 +421,10 @@ int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y) {
     for (int l = 0; l < k_layers; l++) {
       const bool last = l + 1 == k_layers;
       void* out = last ? y : (void*)(s->slot_layer(slot, l + 1) + s->ls.x);
-      if (int rc = layer_forward(s, l, s->slot_layer(slot, l), out, last ? s->c.hidden : s->ld_h)) return rc;
+      char* e = s->slot_layer(slot, l);
+      // with recomputation only x is kept; the layer's other tensors are temporaries in the first scratch entry
+      if (int rc = layer_forward(s, l, e + s->ls.x, s->c.recompute ? s->rc_scratch : e, out, last ? s->c.hidden : s->ld_h))
+        return rc;
     }
   }
   s->slot_k[slot] = k_layers;
@@ -441,13 +469,19 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
     az.clear(); ab.clear(); ao.clear(); aa.clear(); bdy.clear(); bdgu.clear(); bdh.clear(); bdqkv.clear();
     for (int i = 0; i < n; i++) {
       if (k[i] <= l) continue;
+      const char* x = s->slot_layer(slot[i], l) + L.x;
       const char* e = s->slot_layer(slot[i], l);
+      if (c.recompute) {  // rebuild this layer's tensors from its kept input, into scratch entry i
+        char* sc = s->rc_scratch + size_t(i) * L.bytes;
+        if (int rc = layer_forward(s, l, x, sc, nullptr, 0)) return rc;
+        e = sc;
+      }
       const char* dy = pp(i, (l + 1) & 1);
       void* dx = l == 0 ? (void*)((char*)dX + size_t(i) * act) : (void*)pp(i, l & 1);
       s->last_dy = dy;
       s->last_dy_ld = s->ld_h;
       s->last_ws = i;
-      if (int rc = layer_backward_data(s, l, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g)) return rc;
+      if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g)) return rc;
       az.push_back(e + L.z); ab.push_back(e + L.b); ao.push_back(e + L.o); aa.push_back(e + L.a);
       bdy.push_back(dy);
       bdgu.push_back(s->dgu + size_t(i) * s->mb_gu);
@@ -462,6 +496,22 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
   }
   s->head = (s->head + n) % c.max_inflight;
   s->count -= n;
+  return MLS_OK;
+}
+
+int mls_stage_memory(const mls_config* cfg, mls_memory* out) {
+  if (!cfg || !out) return fail(MLS_E_NULL, "mls_stage_memory: null argument");
+  if (int rc = check_config(*cfg)) return rc;
+  mls_stage tmp;
+  tmp.c = *cfg;
+  layout(&tmp);
+  mls_memory m = {};
+  for (const Alloc& al : allocations(&tmp)) (al.kind == 0 ? m.param_bytes : al.kind == 1 ? m.stash_bytes : m.workspace_bytes) += al.bytes;
+  m.total_bytes = m.param_bytes + m.stash_bytes + m.workspace_bytes;
+  m.param_bytes_per_layer = tmp.ilayer_params * tmp.es;
+  m.stash_bytes_per_layer_microbatch = tmp.entry_bytes;
+  m.grad_bytes_per_layer = tmp.layer_params * 4;
+  *out = m;
   return MLS_OK;
 }
 
@@ -554,6 +604,7 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
     if (layer < 0 || layer >= s->slot_k[phys]) return fail(MLS_E_RANGE, "layer out of range for this stash entry");
     const char* e = s->slot_layer(phys, layer);
     const LayerStash& L = s->ls;
+    if (s->c.recompute && id != MLS_T_X) return fail(MLS_E_RANGE, "with recomputation only MLS_T_X is kept");
     switch (id) {
       case MLS_T_X: src = e + L.x; cols = h; ld = s->ld_h; break;
       case MLS_T_A: src = e + L.a; cols = h; ld = s->ld_h; break;

@@ -28,7 +28,7 @@ def test_config_struct_matches_header_field_order():
     body = header[header.index("typedef struct {"):header.index("} mls_config;")]
     fields = re.findall(r"^\s*(?:int32_t|float)\s+(\w+);", body, flags=re.M)
     assert fields == [f[0] for f in mls.MlsConfig._fields_]
-    assert ctypes.sizeof(mls.MlsConfig) == 48
+    assert ctypes.sizeof(mls.MlsConfig) == 52
 
 
 def test_product_package_does_not_import_the_oracle():
