@@ -359,14 +359,17 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
                                                                  const float* __restrict__ lse,
                                                                  const float* __restrict__ delta,
                                                                  bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
-                                                                 int nkv) {
+                                                                 int nkv, int nsplit, float* __restrict__ part) {
   using TL = Tile<D>;
   constexpr bool DKM = WHAT == 0;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];  // [buffer][Q|dO]
   __shared__ float stat[2][2][TR];                                       // [buffer][lse*log2e | delta]
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kb = blockIdx.y, hk = blockIdx.x, bi = blockIdx.z, grp = nq / nkv;
+  // nsplit > 1: the query heads of a group are shared out over nsplit workgroups (few KV heads would otherwise
+  // leave most CUs idle); each writes its fp32 partial sum to `part`, which gqa_reduce_kernel adds up in order
+  const int kb = blockIdx.y, hk = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, bi = blockIdx.z;
+  const int grp = nq / nkv / nsplit, hq0 = hk * (nq / nkv) + sp * grp;
   const bf16_t* base = qkv + int64_t(bi) * S * ld;
   const bf16_t* dob = d_o + int64_t(bi) * S * ldo;
   const int j0 = kb * 128, jw = j0 + wave * 32, ji = jw + (lane & 31);
@@ -393,7 +396,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
   // statistics go through registers (threads 0..63: lse*log2e of row tid; threads 64..127: delta of row tid-64)
   float rs = 0.f;
   auto issue = [&](int it, bool live) {
-    const int hq = hk * grp + (live ? it / nqb : 0), i0 = (qb0 + (live ? it % nqb : 0)) * TR;
+    const int hq = hq0 + (live ? it / nqb : 0), i0 = (qb0 + (live ? it % nqb : 0)) * TR;
     const uint32_t t = lds0 + (it & 1) * 2 * TL::BYTES;
     tq.dma(rq_src, ld, i0, hq * D, t, wave, live);
     td.dma(rd_src, ldo, i0, hq * D, t + TL::BYTES, wave, live);
@@ -470,10 +473,44 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
     if (it + 1 < niter) put_stat(it + 1);
   }
   wait_dma();
-  bf16_t* out = dqkv + int64_t(bi) * S * ldg;
+  if (nsplit == 1) {
+    bf16_t* out = dqkv + int64_t(bi) * S * ldg;
 #pragma unroll
-  for (int t = 0; t < DT; t++)
-    store_t(out, ldg, ji, (DKM ? nq + hk : nq + nkv + hk) * D + t * 32, acc[t], DKM ? scale : 1.f, lane, ji < S);
+    for (int t = 0; t < DT; t++)
+      store_t(out, ldg, ji, (DKM ? nq + hk : nq + nkv + hk) * D + t * 32, acc[t], DKM ? scale : 1.f, lane, ji < S);
+  } else if (ji < S) {
+    // part: [dK | dV][b][n_kv][nsplit][S][D] fp32
+    float* out = part + ((((int64_t(WHAT) * gridDim.z + bi) * nkv + hk) * nsplit + sp) * S + ji) * D;
+    const float mul = DKM ? scale : 1.f;
+#pragma unroll
+    for (int t = 0; t < DT; t++)
+#pragma unroll
+      for (int g = 0; g < 4; g++)
+        *reinterpret_cast<float4*>(out + t * 32 + (lane >> 5) * 4 + 8 * g) =
+            make_float4(acc[t][g * 4] * mul, acc[t][g * 4 + 1] * mul, acc[t][g * 4 + 2] * mul, acc[t][g * 4 + 3] * mul);
+  }
+}
+
+// dK, dV <- the partial sums of the nsplit workgroups of each KV head, added in ascending order (8 features per thread)
+__global__ __launch_bounds__(256) void gqa_reduce_kernel(const float* __restrict__ part, int nsplit, int b, int S, int D,
+                                                         int nq, int nkv, bf16_t* __restrict__ dqkv, int64_t ldg) {
+  const int64_t id = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int cpr = D >> 3;
+  const int64_t total = int64_t(2) * b * nkv * S * cpr;
+  if (id >= total) return;
+  const int c = int(id % cpr) * 8;
+  const int64_t row = id / cpr;               // (what, bi, hk, token)
+  const int token = int(row % S);
+  const int hk = int((row / S) % nkv), bi = int((row / S / nkv) % b), what = int(row / S / nkv / b);
+  const float* p = part + ((((int64_t(what) * b + bi) * nkv + hk) * nsplit) * S + token) * D + c;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int sp = 0; sp < nsplit; sp++) {
+    float v[8];
+    load8(p + int64_t(sp) * S * D, v);
+#pragma unroll
+    for (int e = 0; e < 8; e++) a[e] += v[e];
+  }
+  store8(dqkv + (int64_t(bi) * S + token) * ldg + (what ? nq + nkv + hk : nq + hk) * D + c, a);
 }
 
 }  // namespace
@@ -495,29 +532,53 @@ hipError_t attn_fwd_bf16(const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o,
   return hipGetLastError();
 }
 
+// how many workgroups share the query heads of one KV group in the dK / dV kernels: the smallest divisor of the
+// group size that gives every CU two workgroups (1 when the plain grid already does)
+int gqa_split(int b, int S, int nq, int nkv) {
+  const int grp = nq / nkv, blocks = nkv * ((S + 127) / 128) * b;
+  int n = 1;
+  while (n < grp && blocks * n < 512) {
+    n++;
+    while (grp % n) n++;
+  }
+  return n;
+}
+
+size_t attn_bwd_scratch_floats(int dt, int b, int S, int nq, int nkv, int d) {
+  if (dt != DT_BF16 || nkv <= 0 || nq % nkv) return 0;
+  const int n = gqa_split(b, S, nq, nkv);
+  return n > 1 ? size_t(2) * b * nkv * n * S * d : 0;
+}
+
 hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
                          int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
-                         hipStream_t st) {
+                         hipStream_t st, float* part) {
   if (b == 0 || S == 0) return hipSuccess;
   hipError_t e = attn_delta(DT_BF16, o, ld_o, d_o, ld_do, delta, b, S, nq, d, st);
   if (e != hipSuccess) return e;
-  dim3 gq(nq, (S + 127) / 128, b), gk(nkv, (S + 127) / 128, b);
+  const int ns = part ? gqa_split(b, S, nq, nkv) : 1;
+  dim3 gq(nq, (S + 127) / 128, b), gk(nkv * ns, (S + 127) / 128, b);
   if (d == 128) {
     hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
                        ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
   } else if (d == 64) {
     hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
                        ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
   } else {
     return hipErrorInvalidValue;
+  }
+  if (ns > 1) {
+    const int64_t total = int64_t(2) * b * nkv * S * (d >> 3);
+    hipLaunchKernelGGL(gqa_reduce_kernel, dim3(unsigned((total + 255) / 256)), dim3(256), 0, st, part, ns, b, S, d, nq, nkv,
+                       (bf16_t*)dqkv, ld_dqkv);
   }
   return hipGetLastError();
 }
@@ -529,9 +590,9 @@ hipError_t attn_fwd(int dt, const void* qkv, int64_t ld_qkv, void* o, int64_t ld
 }
 hipError_t attn_bwd(int dt, const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse,
                     const void* d_o, int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq,
-                    int nkv, int d, hipStream_t st) {
+                    int nkv, int d, hipStream_t st, float* part) {
   return dt == DT_BF16
-             ? attn_bwd_bf16(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st)
+             ? attn_bwd_bf16(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st, part)
              : attn_bwd_f32(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st);
 }
 

@@ -66,10 +66,14 @@ hipError_t gu_permute(const void* src, int64_t ld_src, void* dst, int64_t ld_dst
 // (rotary already applied); o: [T, q_dim]; lse: natural-log softmax denominators [b, n_q, S] fp32.
 hipError_t attn_fwd(int dt, const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o, float* lse, int b, int S, int nq,
                     int nkv, int d, hipStream_t st);
-// dqkv has the column layout of qkv; delta: workspace [b, n_q, S] fp32 (row sums of do*o)
+// dqkv has the column layout of qkv; delta: workspace [b, n_q, S] fp32 (row sums of do*o); part: workspace of
+// attn_bwd_scratch_floats() floats, or null.  With few KV heads the dK / dV kernels share the query heads of a
+// group out over several workgroups, which leave fp32 partial sums in `part` for a fixed-order reduction; without
+// the workspace one workgroup walks the whole group.
+size_t attn_bwd_scratch_floats(int dt, int b, int S, int nq, int nkv, int d);
 hipError_t attn_bwd(int dt, const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse,
                     const void* d_o, int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq,
-                    int nkv, int d, hipStream_t st);
+                    int nkv, int d, hipStream_t st, float* part = nullptr);
 
 // pieces behind the two dispatchers above
 hipError_t attn_delta(int dt, const void* o, int64_t ld_o, const void* d_o, int64_t ld_do, float* delta, int b, int S,
@@ -83,6 +87,6 @@ hipError_t attn_fwd_bf16(const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o,
                          int d, hipStream_t st);
 hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
                          int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
-                         hipStream_t st);
+                         hipStream_t st, float* part);
 
 }  // namespace mls

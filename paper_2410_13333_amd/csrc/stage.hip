@@ -108,7 +108,7 @@ struct mls_stage {
   char *g0 = nullptr, *g1 = nullptr, *dz = nullptr, *dgu = nullptr, *dbuf = nullptr, *dh = nullptr, *dc = nullptr,
        *dqkv = nullptr;
   size_t mb_h = 0, mb_gu = 0, mb_qkv = 0;  // bytes per micro-batch of the [T,ld_h], [T,ld_gu], [T,ld_qkv] buffers
-  float *delta = nullptr, *partial = nullptr;
+  float *delta = nullptr, *partial = nullptr, *gqa_part = nullptr;  // gqa_part: partial dK/dV sums (few KV heads)
   const void* last_dy = nullptr;
   int64_t last_dy_ld = 0;
   int last_ws = 0;  // micro-batch workspace used by the most recent layer backward
@@ -244,7 +244,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
   // attention
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
   LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
-                                     s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
+                                     s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st, s->gqa_part));
   LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
                                      c.head_dim, lq, -1.f, s->st));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
@@ -343,12 +343,13 @@ std::vector<Alloc> allocations(mls_stage* s) {
       {(void**)&s->dqkv, nmb * s->mb_qkv, 2},
       {(void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4, 2},
       {(void**)&s->partial, size_t(nb) * h * 4, 2},
+      {(void**)&s->gqa_part, mls::attn_bwd_scratch_floats(s->dt, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) * 4, 2},
   };
 }
 
 void release(mls_stage* s) {
   void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->rc_scratch, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
-               s->delta, s->partial};
+               s->delta, s->partial, s->gqa_part};
   for (void* q : p)
     if (q) (void)hipFree(q);
   for (hipEvent_t e : s->tm.ev) (void)hipEventDestroy(e);
