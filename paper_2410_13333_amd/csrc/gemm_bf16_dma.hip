@@ -14,6 +14,10 @@
 // last substep of tile kt, so no LDS latency is exposed behind the barrier.
 // The LDS-DMA instructions are inline asm because the compiler would otherwise wait for all of them
 // (vmcnt(0)) before every LDS read; the waits are placed by hand.
+// A workgroup is NW wavefronts, 2 along M by NW/2 along N: 4 (one per SIMD, 128x128 of a 256x256 tile each, all
+// accumulators in AGPRs) or 8 (two per SIMD, 128x64 each, under 256 registers, so that one wavefront issues MFMAs
+// while the other waits at the barrier or for its fragments).  bf16 epilogues leave through an LDS staging pass
+// that turns the accumulator layout into whole-row 16-byte accesses.
 #include "common.h"
 #include "kernels.h"
 
