@@ -183,3 +183,38 @@ def test_library_rejects_bad_arguments():
         mls.plan_layers([1.0], -1)
     with pytest.raises(mls.MlsError):
         mls.plan_lower_level([[1.0], []], 4, 4, 1.0)
+
+
+def _golden():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_case_studies.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        kind, cite, inputs, result = [p.strip() for p in line.split("|")]
+        args = {k.strip(): [float(v) for v in vs.split()] for k, vs in (item.split("=") for item in inputs.split(";"))}
+        yield kind, cite, args, [float(v) for v in result.split("=")[1].split()]
+
+
+def test_golden_file_of_printed_values_oracle_and_library():
+    """tests/golden/paper_case_studies.txt holds what the paper prints; both the enumeration and the library must
+    reproduce every record."""
+    import paper_2410_13333_amd as mls
+    seen = 0
+    for kind, cite, a, want in _golden():
+        seen += 1
+        if kind == "microbatches":
+            best, arg = oplan.microbatches_bruteforce(a["o"], int(a["n_mb"][0]))
+            assert arg == [tuple(int(v) for v in want)], cite
+            assert mls.plan_microbatches(a["o"], int(a["n_mb"][0]))[0] == [int(v) for v in want], cite
+        elif kind == "layers":
+            L, printed = int(a["L"][0]), tuple(int(v) for v in want)
+            value = max(y * l for y, l in zip(a["y"], printed))
+            caps = [int(value / y) for y in a["y"]]               # any split at least as good stays under these
+            best, arg = oplan.layers_bruteforce(a["y"], L, caps=caps)
+            assert best == value and printed in arg, cite
+            l, o = mls.plan_layers(a["y"], L)
+            assert o == value and sorted(l) == sorted(printed), cite
+        elif kind == "theoretic":
+            assert abs(mls.theoretic_slowdown(int(a["N"][0]), a["x"]) - want[0]) < 0.006, cite
+    assert seen == 5
