@@ -314,7 +314,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
   const int r32 = lane & 31, hi = lane >> 5;
   const bool col_ok = n0 + wn + cch * 8 < N;        // N is a multiple of 8
   const int ccol = col0 + n0 + wn + cch * 8;        // first column of this lane's chunk, in the whole problem
-  auto stage_at = [&](int row, int chunk) { return ws + row * RB + ((chunk ^ (row & (NCH - 1))) << 4); };
+  // rows of RB < 256 bytes share a 256-byte bank line: the swizzle key is the line, so that the 32 rows of an
+  // accumulator-layout access fall on every bank equally often
+  constexpr int RPL = RB < 256 ? 256 / RB : 1;
+  auto stage_at = [&](int row, int chunk) { return ws + row * RB + ((chunk ^ ((row / RPL) & (NCH - 1))) << 4); };
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     const int row0 = m0 + wm + i * 32;
@@ -346,7 +349,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
         wave_lds_sync();
       }
       // combine in the accumulator layout, in place
-      constexpr int ZRB = CW, ZNCH = ZRB / 16;  // SwiGLU product: half as many columns, staged behind the 8 KiB
+      constexpr int ZRB = CW, ZNCH = ZRB / 16, ZRPL = ZRB < 256 ? 256 / ZRB : 1;  // SwiGLU product: half as many columns, staged behind the 8 KiB
       unsigned char* wz = ws + 32 * RB;
 #pragma unroll
       for (int q = 0; q < TN * 4; q++) {
@@ -377,7 +380,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
           zo.x = pack_bf16x2(z[0], z[1]);
           zo.y = pack_bf16x2(z[2], z[3]);
           const int zc = 4 * (j >> 1) + g;
-          *reinterpret_cast<uint2*>(wz + r32 * ZRB + ((zc ^ (r32 & (ZNCH - 1))) << 4) + hi * 8) = zo;
+          *reinterpret_cast<uint2*>(wz + r32 * ZRB + ((zc ^ ((r32 / ZRPL) & (ZNCH - 1))) << 4) + hi * 8) = zo;
         }
       }
       wave_lds_sync();
@@ -395,7 +398,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
 #pragma unroll
         for (int t = 0; t < ZNT; t++) {
           const int lrow = t * ZRPI + zrow, row = row0 + lrow;
-          const uint4 o = *reinterpret_cast<const uint4*>(wz + lrow * ZRB + ((zch ^ (lrow & (ZNCH - 1))) << 4));
+          const uint4 o = *reinterpret_cast<const uint4*>(wz + lrow * ZRB + ((zch ^ ((lrow / ZRPL) & (ZNCH - 1))) << 4));
           if (row < M && z_ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(Xv) + int64_t(row) * ldx + zcol) = o;
         }
       }
