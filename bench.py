@@ -228,10 +228,11 @@ def main():
     grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
 
     def step():
-        grads.zero_()
+        # one backward call per step: it writes the gradients (MLS_BWD_OVERWRITE) instead of adding to a vector the
+        # harness would have to zero first; the result is bit-identical to zeroing and accumulating
         for mb in range(M):
             st.forward(xs[mb], K, ys[mb])
-        st.backward(dy, grads, M, dx)
+        st.backward(dy, grads, M, dx, overwrite=True)
 
     for _ in range(a.warmup):
         step()

@@ -121,6 +121,14 @@ int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y);
  * MLS_E_STASH (n exceeds the stashed entries), MLS_E_HIP. */
 int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n_microbatches, void* dX);
 
+/* mls_stage_backward with flags.  MLS_BWD_OVERWRITE: `grads` is written, not added to -- every layer some entry of
+ * this call reached receives exactly the gradient of this call (bit-identical to zeroing grads and calling
+ * mls_stage_backward), all other layers up to max_layers are set to zero; the fp32 gradient vector is then never
+ * read, which saves the caller's zeroing pass and the read half of the accumulation (n = 0 zeroes everything).
+ * Use it for the first backward call of a step and plain accumulation for the following ones. */
+enum { MLS_BWD_OVERWRITE = 1 };
+int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n_microbatches, void* dX, int32_t flags);
+
 /* Release everything the handle owns (synchronises the stream first).  NULL is allowed. */
 void mls_stage_free(mls_stage* s);
 

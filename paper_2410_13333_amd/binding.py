@@ -63,6 +63,7 @@ def lib():
         vp, i32, i64, u64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_size_t
         L.mls_stage_init.argtypes = [C.POINTER(MlsConfig), u64, vp, C.POINTER(vp)]
         L.mls_stage_forward.argtypes = [vp, vp, i32, vp]
+        L.mls_stage_backward_ex.argtypes = [vp, vp, vp, i32, vp, i32]
         L.mls_stage_backward.argtypes = [vp, vp, vp, i32, vp]
         L.mls_stage_free.argtypes = [vp]
         L.mls_stage_free.restype = None
@@ -172,8 +173,12 @@ class Stage:
     def forward(self, x, k_layers, y):
         _check(lib().mls_stage_forward(self._h, _ptr(x), k_layers, _ptr(y)))
 
-    def backward(self, dy, grads, n_microbatches, dx):
-        _check(lib().mls_stage_backward(self._h, _ptr(dy), _ptr(grads), n_microbatches, _ptr(dx)))
+    def backward(self, dy, grads, n_microbatches, dx, overwrite=False):
+        """overwrite=True: grads is written instead of added to (MLS_BWD_OVERWRITE)."""
+        if overwrite:
+            _check(lib().mls_stage_backward_ex(self._h, _ptr(dy), _ptr(grads), n_microbatches, _ptr(dx), 1))
+        else:
+            _check(lib().mls_stage_backward(self._h, _ptr(dy), _ptr(grads), n_microbatches, _ptr(dx)))
 
     # ---- support
     @property

@@ -120,7 +120,7 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
 
 // out[c] += sum_b partial[b][c]: 16 columns per workgroup, 16 row groups per column, fixed summation order
 __global__ __launch_bounds__(256) void colsum_add_kernel(const float* __restrict__ partial, float* __restrict__ out,
-                                                         int nblocks, int h) {
+                                                         int nblocks, int h, bool overwrite) {
   __shared__ float red[16][17];
   const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + cl;
@@ -133,8 +133,13 @@ __global__ __launch_bounds__(256) void colsum_add_kernel(const float* __restrict
     float t = 0.f;
 #pragma unroll
     for (int g = 0; g < 16; g++) t += red[g][cl];
-    out[c] += t;
+    out[c] = overwrite ? t : out[c] + t;
   }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float4* __restrict__ p, size_t n4) {
+  const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // ---------------------------------------------------------------- rotary embedding, in place
@@ -288,7 +293,7 @@ int rmsnorm_bwd_blocks(int T) { return T < 512 ? (T > 0 ? T : 1) : 512; }
 
 hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
                        const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
-                       float* partial, int T, int h, hipStream_t st) {
+                       float* partial, int T, int h, hipStream_t st, bool overwrite) {
   if (T == 0) return hipSuccess;
   const int nb = rmsnorm_bwd_blocks(T);
 #define BWD(TY, C)                                                                                               \
@@ -303,7 +308,15 @@ hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int
 #undef BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 15) / 16), dim3(256), 0, st, partial, dgamma, nb, h);
+  hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 15) / 16), dim3(256), 0, st, partial, dgamma, nb, h, overwrite);
+  return hipGetLastError();
+}
+
+// n floats (a multiple of 4, 16-byte aligned) <- 0, as a kernel (safe to record into a HIP graph)
+hipError_t fill_zero_f32(float* p, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (n % 4 || (uintptr_t(p) & 15)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(unsigned((n / 4 + 255) / 256)), dim3(256), 0, st, reinterpret_cast<float4*>(p), n / 4);
   return hipGetLastError();
 }
 

@@ -24,8 +24,8 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-// Epilogues.  EPI_BF16: C = acc (+ R), bf16.  EPI_F32_ACC: C += acc, fp32; with `xf` > 0 the columns are the
-// gate/up-interleaved order and are written to their public places (see gu_public_col).  EPI_SWIGLU: N = 2f
+// Epilogues.  EPI_BF16: C = acc (+ R), bf16.  EPI_F32_ACC: C += acc, fp32 (C = acc when `ldx` != 0); with `xf` > 0
+// the columns are the gate/up-interleaved order and are written to their public places (see gu_public_col).  EPI_SWIGLU: N = 2f
 // interleaved columns [gate | up]; C receives both (bf16) and X[row][f] their SwiGLU product.  (The SwiGLU backward
 // as an epilogue of the dZ contraction was measured slower than a separate kernel: the epilogue's extra reads are
 // fully exposed with one workgroup per CU.)
@@ -332,7 +332,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
           if (col >= N) continue;
           float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + int64_t(row) * ldc +
                                                 (xf > 0 ? gu_public_col(col0 + col, xf) : col0 + col));
-          float4 t = *c;
+          float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (ldx == 0) t = *c;  // ldx != 0 in this mode: store, do not accumulate (C is not read)
           t.x += acc[i][j][g * 4]; t.y += acc[i][j][g * 4 + 1]; t.z += acc[i][j][g * 4 + 2]; t.w += acc[i][j][g * 4 + 3];
           *c = t;
         }
@@ -518,7 +519,7 @@ bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb) { return gemm_bf16_
 // C[M,N] += sum_i A_i[kseg,M]^T * B_i[kseg,N] (fp32 C), the contraction of all pieces accumulated in registers and
 // added to C once: the weight gradient of several micro-batches in one launch.  nseg <= 16.
 hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
-                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f) {
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f, bool overwrite) {
   if (M == 0 || N == 0 || nseg == 0 || kseg == 0) return hipSuccess;
   if (nseg > MAX_SEGS || (gu_f > 0 && (gu_f % 32 || N != 2 * gu_f))) return hipErrorInvalidValue;
   SegArgs sa = {};
@@ -534,18 +535,18 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
       hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
-          sa.a[0], sa.b[0], C, nullptr, M, n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0, gu_f);
+          sa.a[0], sa.b[0], C, nullptr, M, n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0, gu_f);
       if (e != hipSuccess) return e;
       for (int i = 0; i < nseg; i++) sa.b[i] += n1;
       return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
-          sa.a[0], sa.b[0], C, nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, n1, nullptr, 0, gu_f);
+          sa.a[0], sa.b[0], C, nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, n1, nullptr, overwrite ? 1 : 0, gu_f);
     }
     return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
-                                                                              ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0,
+                                                                              ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0,
                                                                               gu_f);
   }
   return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
-                                                                             ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, 0,
+                                                                             ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0,
                                                                              gu_f);
 }
 

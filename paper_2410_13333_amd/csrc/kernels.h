@@ -25,8 +25,11 @@ hipError_t gemm_bf16_dma(int mode, const void* A, const void* B, void* C, const 
 // at most 16 pieces, all with the same strides; true if the operands fit the DMA path's 31-bit offsets
 bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb);
 // gu_f > 0: the N = 2 gu_f columns of the B pieces are in the interleaved gate/up order and C is in the public one
+// overwrite: C = instead of C += (the fp32 gradient is then not read)
 hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
-                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f = 0);
+                                 int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f = 0,
+                                 bool overwrite = false);
+hipError_t fill_zero_f32(float* p, size_t n, hipStream_t st);
 // SwiGLU fused into the gate/up contraction (bf16, f % 32 == 0, DMA path).  Interleaved gate/up column order:
 // 32 gate columns, the 32 up columns of the same indices, and so on (gu_interleaved_col in common.h).
 //   GU[M, 2f] = A[M,K] W[K, 2f] (W and GU interleaved), Z[M, f] = silu(gate) * up
@@ -43,10 +46,11 @@ hipError_t rmsnorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, vo
                        int h, float eps, hipStream_t st);
 // dx = dres + r*(dn - n*mean(dn*n)), dn = da*gamma, n = x*r;  dgamma += sum_t da*n (two-stage, deterministic).
 // partial: workspace of rmsnorm_bwd_blocks(T) * h floats.  dres may be null (no residual branch: dx without it).
+// overwrite: dgamma = instead of +=.
 int rmsnorm_bwd_blocks(int T);
 hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
                        const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
-                       float* partial, int T, int h, hipStream_t st);
+                       float* partial, int T, int h, hipStream_t st, bool overwrite = false);
 // rotate the pairs (i, i+d/2) of the first n_heads heads of every row of u [T, ld] by sign*angle(t % S, i)
 hipError_t rope_inplace(int dt, void* u, const float* cos_tab, const float* sin_tab, int T, int S, int n_heads, int d,
                         int64_t ld, float sign, hipStream_t st);

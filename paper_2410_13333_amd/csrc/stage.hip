@@ -227,7 +227,7 @@ int layer_forward(mls_stage* s, int layer, const char* x, char* e, void* out, in
 // dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the gradient w.r.t. its input (row stride
 // ld_dx); g: this layer's slice of the caller's fp32 gradient vector (gains only here).
 int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, int w, const void* dy, int64_t ld_dy,
-                        void* dx, int64_t ld_dx, float* g) {
+                        void* dx, int64_t ld_dx, float* g, bool ow) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, wq = s->qkvw;
@@ -240,7 +240,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
   LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st, s->fuse_gu));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
-                                    dy, ld_dy, dh, lh, g + s->off_g2, s->partial, T, h, s->st));
+                                    dy, ld_dy, dh, lh, g + s->off_g2, s->partial, T, h, s->st, ow));
   // attention
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
   LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
@@ -249,18 +249,20 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
                                      c.head_dim, lq, -1.f, s->st));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
-                                    dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st));
+                                    dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st, ow));
   return MLS_OK;
 }
 
 // C[M,N] += sum_i A_i[T,M]^T B_i[T,N] over n micro-batches (fp32 C): one launch per 16 micro-batches on the bf16
 // DMA path, one launch per micro-batch otherwise
 int wgrad(mls_stage* s, const void* const* A, const void* const* B, int n, float* C, int M, int N, int64_t lda,
-          int64_t ldb, int gu_f = 0) {
+          int64_t ldb, int gu_f, bool ow) {
   if (s->dt == mls::DT_BF16 && mls::gemm_tn_segments_ok(s->T, lda, ldb)) {  // always true when gu_f > 0
     for (int i = 0; i < n; i += 16)
-      LAUNCH(CLS_GEMM_TN, mls::gemm_bf16_tn_segments(A + i, B + i, n - i < 16 ? n - i : 16, C, M, N, s->T, lda, ldb, N, s->st, gu_f));
+      LAUNCH(CLS_GEMM_TN, mls::gemm_bf16_tn_segments(A + i, B + i, n - i < 16 ? n - i : 16, C, M, N, s->T, lda, ldb, N, s->st,
+                                                     gu_f, ow && i == 0));
   } else {
+    if (ow) HIP_TRY(mls::fill_zero_f32(C, size_t(M) * N, s->st));  // this path only accumulates
     for (int i = 0; i < n; i++) LAUNCH(CLS_GEMM_TN, gemm(s, mls::GEMM_TN, A[i], B[i], C, nullptr, M, N, s->T, lda, ldb, N));
   }
   return MLS_OK;
@@ -434,10 +436,16 @@ int mls_stage_forward(mls_stage* s, const void* x, int32_t k_layers, void* y) {
 }
 
 int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, void* dX) {
+  return mls_stage_backward_ex(s, dY, grads, n, dX, 0);
+}
+
+int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n, void* dX, int32_t flags) {
   if (!s) return fail(MLS_E_NULL, "mls_stage_backward: null handle");
+  if (flags & ~MLS_BWD_OVERWRITE) return fail(MLS_E_CONFIG, "mls_stage_backward_ex: unknown flag");
+  const bool ow = (flags & MLS_BWD_OVERWRITE) != 0;
   if (n < 0) return fail(MLS_E_RANGE, "n_microbatches must be >= 0");
-  if (n == 0) return MLS_OK;
-  if (!dY || !dX || !grads) return fail(MLS_E_NULL, "mls_stage_backward: null argument");
+  if (n == 0 && !ow) return MLS_OK;
+  if (!grads || (n > 0 && (!dY || !dX))) return fail(MLS_E_NULL, "mls_stage_backward: null argument");
   if ((uintptr_t(dY) | uintptr_t(dX) | uintptr_t(grads)) & 15)
     return fail(MLS_E_CONFIG, "mls_stage_backward: dY, dX and grads must be 16-byte aligned");
   if (n > s->count) return fail(MLS_E_STASH, "n_microbatches exceeds the stashed micro-batches");
@@ -482,7 +490,7 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
       s->last_dy = dy;
       s->last_dy_ld = s->ld_h;
       s->last_ws = i;
-      if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g)) return rc;
+      if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g, ow && az.empty())) return rc;
       az.push_back(e + L.z); ab.push_back(e + L.b); ao.push_back(e + L.o); aa.push_back(e + L.a);
       bdy.push_back(dy);
       bdgu.push_back(s->dgu + size_t(i) * s->mb_gu);
@@ -490,11 +498,14 @@ int mls_stage_backward(mls_stage* s, const void* dY, float* grads, int32_t n, vo
       bdqkv.push_back(s->dqkv + size_t(i) * s->mb_qkv);
     }
     const int m = (int)az.size();
-    if (int rc = wgrad(s, az.data(), bdy.data(), m, g + s->off_wd, f, h, s->ld_f, s->ld_h)) return rc;
-    if (int rc = wgrad(s, ab.data(), bdgu.data(), m, g + s->off_wgu, h, 2 * f, s->ld_h, s->ld_gu, s->fuse_gu ? f : 0)) return rc;
-    if (int rc = wgrad(s, ao.data(), bdh.data(), m, g + s->off_wo, s->qd, h, s->ld_qd, s->ld_h)) return rc;
-    if (int rc = wgrad(s, aa.data(), bdqkv.data(), m, g + s->off_wqkv, h, s->qkvw, s->ld_h, s->ld_qkv)) return rc;
+    if (int rc = wgrad(s, az.data(), bdy.data(), m, g + s->off_wd, f, h, s->ld_f, s->ld_h, 0, ow)) return rc;
+    if (int rc = wgrad(s, ab.data(), bdgu.data(), m, g + s->off_wgu, h, 2 * f, s->ld_h, s->ld_gu, s->fuse_gu ? f : 0, ow)) return rc;
+    if (int rc = wgrad(s, ao.data(), bdh.data(), m, g + s->off_wo, s->qd, h, s->ld_qd, s->ld_h, 0, ow)) return rc;
+    if (int rc = wgrad(s, aa.data(), bdqkv.data(), m, g + s->off_wqkv, h, s->qkvw, s->ld_h, s->ld_qkv, 0, ow)) return rc;
   }
+  // overwrite mode: the layers no entry of this call reached hold no gradient
+  if (ow && kmax < c.max_layers)
+    HIP_TRY(mls::fill_zero_f32(grads + size_t(kmax) * s->layer_params, size_t(c.max_layers - kmax) * s->layer_params, s->st));
   s->head = (s->head + n) % c.max_inflight;
   s->count -= n;
   return MLS_OK;

@@ -213,3 +213,42 @@ def test_wide_hidden_rows_span_many_chunks():
                               layers=1, microbatches=2)
         _check(sh, [1, 1], 1e-2)
         _check(sh.with_(dtype="fp32"), [1], 1e-4)
+
+
+@pytest.mark.parametrize("base", ["ragged", "fused", "fp32"])
+def test_overwrite_mode_equals_zeroing_then_accumulating(base):
+    """MLS_BWD_OVERWRITE: a gradient vector full of NaN goes in, exactly the gradients of zero-then-accumulate come
+    out, layers no entry reached are zero, and a following plain call accumulates on top."""
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = {"ragged": RAGGED, "fused": FUSED_RAGGED, "fp32": RAGGED.with_(dtype="fp32")}[base].with_(layers=4)
+    ks = [2, 3, 0, 1]
+    ref = gpu_step(sh, 1000, 2000, 3000, ks)
+    ref[3].close()
+    st = mls.Stage.from_shape(sh, seed=1000, max_inflight=len(ks))
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    xs = [to_device(synth.make_x(sh, 2000, mb)[0], sh.dtype) for mb in range(len(ks))]
+    dy = torch.stack([to_device(synth.make_dy(sh, 3000, mb)[0], sh.dtype) for mb in range(len(ks))])
+    ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in ks]
+    dx = torch.empty_like(dy)
+    grads = torch.full((st.grad_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    for mb, k in enumerate(ks):
+        st.forward(xs[mb], k, ys[mb])
+    st.backward(dy, grads, len(ks), dx, overwrite=True)
+    torch.cuda.synchronize()
+    g = to_host64(grads)
+    assert np.array_equal(g, ref[2])
+    per = synth.layer_param_elems(sh)
+    assert not g[3 * per:].any() and g[2 * per:3 * per].any()          # layer 3 untouched, layer 2 reached by one entry
+    for u, v in zip(ref[1], dx):
+        assert np.array_equal(u, to_host64(v))
+    # a second, plain call adds the same gradients once more
+    for mb, k in enumerate(ks):
+        st.forward(xs[mb], k, ys[mb])
+    st.backward(dy, grads, len(ks), dx)
+    torch.cuda.synchronize()
+    assert rel_err(to_host64(grads), 2 * ref[2]) < 1e-6
+    st.backward(dy, grads, 0, dx, overwrite=True)                       # nothing to pop: everything zero
+    torch.cuda.synchronize()
+    assert not to_host64(grads).any()
+    st.close()
