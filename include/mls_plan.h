@@ -59,6 +59,21 @@ int64_t mls_plan_layer_cap(double a_f, double a_fb, double s, double nu, int32_t
  * limit, real-valued assignments) = (sum 1/y2) / (sum 1/y1).  NaN on bad input. */
 double mls_grouping_time_ratio(const double* y1, int32_t n1, const double* y2, int32_t n2);
 
+/* Group splitting (Sec. 4.3.1; Appendix B.7): n GPUs of one node with straggling rates x[n] are to form k groups of
+ * sizes[k] GPUs (sum of sizes = n), e.g. the 7 GPUs left after isolating a heavy straggler into groups of 1, 2, 4.
+ * By the appendix's proposition an optimal grouping puts GPUs that are consecutive in the order of their rates into
+ * the same group, so the candidates are: sort by rate, cut into consecutive runs, one run per group, for every
+ * order of the groups along the sorted list (6 candidates for sizes 1, 2, 4).  The rate of a group is
+ * y = rho[g] * max x over its members (rho[g]: the efficiency coefficient rho_n of a group of sizes[g] GPUs,
+ * Sec. 4.2); the candidate with the largest sum of 1/y wins (Theorem 2: training time is proportional to the
+ * inverse of that sum).  Ties: the candidate that comes first when the orders of the groups are enumerated
+ * lexicographically.
+ *   group_of[n]  (out) index into sizes[] of the group each GPU joins
+ *   inv_sum      (out, may be NULL) sum over the groups of 1 / y for the winner
+ * k <= 8.  MLS_E_CONFIG on bad sizes or rates. */
+int mls_plan_split_groups(const double* x, int32_t n, const int32_t* sizes, const double* rho, int32_t k,
+                          int32_t* group_of, double* inv_sum);
+
 /* Sec. 7.2: best possible ratio of the step time with stragglers to the step time without, for N GPUs of which n
  * straggle with rates x[n]: N / ((N - n) + sum 1/x).  NaN on bad input. */
 double mls_theoretic_slowdown(int64_t N, const double* x, int32_t n);

@@ -73,3 +73,35 @@ def relaxed_time(y, L=1.0):
 
 def sorted_loads(y, l):
     return tuple(sorted((yj * lj for yj, lj in zip(y, l)), reverse=True))
+
+
+def split_groups_bruteforce(x, sizes, rho):
+    """Group splitting (Sec. 4.3.1, Appendix B.7) without the appendix's proposition: EVERY assignment of the GPUs to
+    groups of the given sizes; returns the largest sum over groups of 1 / (rho_g * max x in the group)."""
+    n = len(x)
+    assert sum(sizes) == n
+    best = None
+
+    def rec(g, free, acc):
+        nonlocal best
+        if g == len(sizes):
+            if best is None or acc > best:
+                best = acc
+            return
+        for members in itertools.combinations(sorted(free), sizes[g]):
+            rec(g + 1, free - set(members), acc + 1.0 / (rho[g] * max(x[i] for i in members)))
+    rec(0, set(range(n)), 0.0)
+    return best
+
+
+def consecutive_run_candidates(n, sizes):
+    """The candidate groupings of Appendix B.7 for GPUs already sorted by descending rate: one tuple of index runs per
+    order of the groups."""
+    out = []
+    for order in sorted(set(itertools.permutations(range(len(sizes))))):
+        at, runs = 0, [None] * len(sizes)
+        for g in order:
+            runs[g] = tuple(range(at, at + sizes[g]))
+            at += sizes[g]
+        out.append(tuple(runs))
+    return out

@@ -112,6 +112,7 @@ def lib():
         L.mls_plan_layers.argtypes = [dp_, ip_, i32, i64, ip_, dp_]
         L.mls_plan_microbatches.argtypes = [dp_, i32, i64, ip_, dp_]
         L.mls_plan_lower_level.argtypes = [dp_, ip_, C.POINTER(i32), i32, i64, i64, C.c_double, ip_, ip_, dp_]
+        L.mls_plan_split_groups.argtypes = [dp_, i32, C.POINTER(i32), dp_, i32, C.POINTER(i32), dp_]
         L.mls_plan_layer_cap.argtypes = [C.c_double] * 4 + [i32, i32, C.c_double, C.c_double]
         L.mls_plan_layer_cap.restype = i64
         L.mls_grouping_time_ratio.argtypes = [dp_, i32, dp_, i32]
@@ -458,6 +459,15 @@ def plan_lower_level(pipelines, L, n_mb, tau, caps=None):
 def plan_layer_cap(a_f, a_fb, s, nu, pp, j, capacity, reserve=0.0):
     """Appendix B.4: most layers stage j of pp can hold under the linear memory model."""
     return lib().mls_plan_layer_cap(a_f, a_fb, s, nu, pp, j, capacity, reserve)
+
+
+def plan_split_groups(x, sizes, rho):
+    """Appendix B.7: best consecutive-run grouping of GPUs with rates x into groups of the given sizes; returns
+    (group index per GPU, sum of 1/y)."""
+    n, k = len(x), len(sizes)
+    out, s = (C.c_int32 * n)(), C.c_double()
+    _check(lib().mls_plan_split_groups(_darr(x), n, (C.c_int32 * k)(*sizes), _darr(rho), k, out, C.byref(s)))
+    return list(out), s.value
 
 
 def grouping_time_ratio(y1, y2):

@@ -140,6 +140,47 @@ int64_t mls_plan_layer_cap(double a_f, double a_fb, double s, double nu, int32_t
   return int64_t(std::floor(room / mu));
 }
 
+int mls_plan_split_groups(const double* x, int32_t n, const int32_t* sizes, const double* rho, int32_t k,
+                          int32_t* group_of, double* inv_sum) {
+  if (!x || !sizes || !rho || !group_of) return mls::set_error(MLS_E_NULL, "mls_plan_split_groups: null argument");
+  if (n < 1 || k < 1 || k > 8 || !rates_ok(x, n) || !rates_ok(rho, k))
+    return mls::set_error(MLS_E_CONFIG, "mls_plan_split_groups: need n >= 1, 1 <= k <= 8 and finite rates > 0");
+  int64_t total = 0;
+  for (int g = 0; g < k; g++) {
+    if (sizes[g] < 1) return mls::set_error(MLS_E_CONFIG, "mls_plan_split_groups: group sizes must be positive");
+    total += sizes[g];
+  }
+  if (total != n) return mls::set_error(MLS_E_CONFIG, "mls_plan_split_groups: the group sizes must add up to n");
+  // GPUs in descending order of their rates (stable: equal rates keep their index order)
+  std::vector<int> by_rate(n);
+  for (int i = 0; i < n; i++) by_rate[i] = i;
+  std::stable_sort(by_rate.begin(), by_rate.end(), [&](int a, int b) { return x[a] > x[b]; });
+  std::vector<int> order(k), best_order;
+  for (int g = 0; g < k; g++) order[g] = g;
+  double best = -1.0;
+  do {  // order[p] = the group that takes the p-th run of the sorted list
+    double sum = 0.0;
+    int at = 0;
+    for (int p = 0; p < k; p++) {
+      const int g = order[p];
+      sum += 1.0 / (rho[g] * x[by_rate[at]]);  // the run's first GPU has its largest rate
+      at += sizes[g];
+    }
+    if (sum > best) {
+      best = sum;
+      best_order = order;
+    }
+  } while (std::next_permutation(order.begin(), order.end()));
+  int at = 0;
+  for (int p = 0; p < k; p++) {
+    const int g = best_order[p];
+    for (int i = 0; i < sizes[g]; i++) group_of[by_rate[at + i]] = g;
+    at += sizes[g];
+  }
+  if (inv_sum) *inv_sum = best;
+  return MLS_OK;
+}
+
 double mls_grouping_time_ratio(const double* y1, int32_t n1, const double* y2, int32_t n2) {
   if (!y1 || !y2 || n1 < 1 || n2 < 1 || !rates_ok(y1, n1) || !rates_ok(y2, n2)) return std::nan("");
   double s1 = 0, s2 = 0;

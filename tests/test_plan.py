@@ -218,3 +218,36 @@ def test_golden_file_of_printed_values_oracle_and_library():
         elif kind == "theoretic":
             assert abs(mls.theoretic_slowdown(int(a["N"][0]), a["x"]) - want[0]) < 0.006, cite
     assert seen == 5
+
+
+def test_oracle_split_candidates_are_the_six_of_the_appendix():
+    """Appendix B.7 lists, for 7 GPUs X1..X7 in descending rate and groups Y1, Y2, Y3 of 1, 2, 4 GPUs, exactly these
+    six groupings (1-based GPU numbers as printed)."""
+    printed = {((1,), (2, 3), (4, 5, 6, 7)), ((1,), (6, 7), (2, 3, 4, 5)), ((3,), (1, 2), (4, 5, 6, 7)),
+               ((5,), (6, 7), (1, 2, 3, 4)), ((7,), (1, 2), (3, 4, 5, 6)), ((7,), (5, 6), (1, 2, 3, 4))}
+    got = {tuple(tuple(i + 1 for i in run) for run in cand) for cand in oplan.consecutive_run_candidates(7, [1, 2, 4])}
+    assert got == printed
+
+
+def test_split_groups_library_matches_exhaustive_search():
+    """The appendix's proposition (an optimum uses consecutive runs) and the library's pick, against the search over
+    every assignment; rates include the three stragglers of the appendix's experiment (2.57, 5.42, 12.53)."""
+    import paper_2410_13333_amd as mls
+    rng = random.Random(23)
+    cases = [([12.53, 5.42, 2.57, 1.0, 1.0, 1.0, 1.0], [1, 2, 4], [1.0, 0.55, 0.3])]
+    for _ in range(40):
+        sizes = rng.choice([[1, 2, 4], [1, 1, 2], [2, 2], [1, 2, 2, 2], [4, 2, 1], [1, 1, 1, 1]])
+        x = [rng.choice([1.0, 1.0, 1.0, 1.31, 2.57, 2.62, 3.75, 5.42, 12.53]) for _ in range(sum(sizes))]
+        rho = [{1: 1.0, 2: 0.55, 4: 0.3}[s] * rng.choice([1.0, 1.1]) for s in sizes]
+        cases.append((x, sizes, rho))
+    for x, sizes, rho in cases:
+        want = oplan.split_groups_bruteforce(x, sizes, rho)
+        group_of, inv = mls.plan_split_groups(x, sizes, rho)
+        assert sorted(group_of.count(g) for g in range(len(sizes))) == sorted(sizes)
+        assert [group_of.count(g) for g in range(len(sizes))] == sizes
+        got = sum(1.0 / (rho[g] * max(xi for xi, gi in zip(x, group_of) if gi == g)) for g in range(len(sizes)))
+        assert got == pytest.approx(inv, rel=1e-14) and inv == pytest.approx(want, rel=1e-12)
+    # first case: the two heaviest stragglers share the pair, the third stands alone, the healthy four stay together
+    assert mls.plan_split_groups(*cases[0])[0] == [1, 1, 0, 2, 2, 2, 2]
+    with pytest.raises(mls.MlsError):
+        mls.plan_split_groups([1.0, 1.0], [1, 2], [1.0, 1.0])
