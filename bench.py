@@ -190,12 +190,72 @@ def run_optim(steps, warmup):
     return out
 
 
+def run_model(steps, warmup, n_mb=4):
+    """A complete training step of a 4-layer model of the 7B layer shape on one GPU: token embedding, the decoder
+    stage, final RMSNorm + LM head + loss, their backwards over n_mb accumulated micro-batches, and the AdamW update of
+    all parameters (stage: 809.5 M, embedding + head: 262.1 M).  Reported beside the headline stage metric."""
+    import torch
+    import synth
+    import paper_2410_13333_amd as mls
+    sh = synth.CONFIGS["7b"].with_(microbatches=n_mb)
+    esh = synth.ENDS_CONFIGS["7b"].with_(microbatches=n_mb)
+    st = mls.Stage.from_shape(sh, seed=1001)
+    en = mls.Ends.from_shape(esh, seed=1101)
+    ps, pe = st.get_params(), en.get_params()
+    os_, oe_ = mls.Optim(ps), mls.Optim(pe)
+    toks = [torch.from_numpy(synth.make_tokens(esh, 2100, mb).reshape(-1)).cuda() for mb in range(n_mb)]
+    tgts = [torch.from_numpy(synth.make_targets(esh, 2200, mb).reshape(-1)).cuda() for mb in range(n_mb)]
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    x = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(n_mb)]
+    y = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(n_mb)]
+    dy = torch.empty((n_mb,) + shape, dtype=st.tdtype, device="cuda")
+    dx = torch.empty_like(dy)
+    loss = torch.zeros(n_mb, dtype=torch.float32, device="cuda")
+    gs = torch.empty(st.grad_elems, dtype=torch.float32, device="cuda")
+    ge = torch.zeros(en.grad_elems, dtype=torch.float32, device="cuda")
+    losses = []
+
+    def step():
+        ge.zero_()
+        for mb in range(n_mb):
+            en.embed_forward(toks[mb], x[mb])
+            st.forward(x[mb], sh.layers, y[mb])
+            en.head_forward(y[mb], tgts[mb], 1.0 / n_mb, loss[mb:mb + 1])
+        en.head_backward(ge, n_mb, dy)
+        st.backward(dy, gs, n_mb, dx, overwrite=True)
+        en.embed_backward(dx, ge, n_mb)
+        os_.step(gs, ps, lr=3e-4)
+        oe_.step(ge, pe, lr=3e-4)
+        st.set_params(ps)
+        en.set_params(pe)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+        losses.append(loss.mean())
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flops = (sh.model_flops_layer_mb() * sh.layers + esh.model_flops_mb()) * n_mb
+    out = {"metric": "model step fwd+bwd+update TFLOP/s (bf16)", "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"4-layer model of the 7B layer shape (vocabulary 32000), {n_mb} micro-batches of 4096 "
+                                  f"tokens, AdamW on all 1.07 G parameters"},
+           "tokens_per_s": n_mb * sh.tokens / (ms * 1e-3),
+           "loss_first_last": [float(losses[0]), float(losses[-1])]}
+    for h in (os_, oe_, st, en):
+        h.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step)")
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step), model (embedding + stage + head + update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--recompute", action="store_true", help="activation recomputation: keep only the layer inputs")
     a = ap.parse_args()
@@ -206,6 +266,9 @@ def main():
         return plan_sweep(a)
     if a.workload == "ends":
         print(json.dumps(run_ends(a.steps, a.warmup)))
+        return
+    if a.workload == "model":
+        print(json.dumps(run_model(a.steps, a.warmup)))
         return
     if a.workload == "optim":
         print(json.dumps(run_optim(a.steps, a.warmup)))
