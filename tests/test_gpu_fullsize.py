@@ -1,4 +1,4 @@
-"""Full-size parity: one layer x one micro-batch at the real 7B and 70B-shard (grouped KV heads) shapes, i.e.
+"""Full-size parity: one layer x one micro-batch at the real 7B, 13B and 70B-shard (grouped KV heads) shapes, i.e.
 every kernel in exactly the launch configuration the benchmark times, compared with the fp64 oracle on the
 same seeded bf16 inputs: the full y, dX and every parameter gradient (tolerance 1e-2, relative Frobenius)."""
 import time
@@ -12,7 +12,7 @@ from tests.helpers import bf16_store, gpu_step, grad_errors, oracle_step, rel_er
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["7b", "70b_tp4"])
+@pytest.mark.parametrize("name", ["7b", "13b", "70b_tp4"])
 @pytest.mark.timeout(400)
 def test_full_shape_single_layer(name):
     sh = synth.CONFIGS[name].with_(layers=1, microbatches=1)
@@ -26,11 +26,12 @@ def test_full_shape_single_layer(name):
     ref_bits, _ = synth.round_to_storage(p64[:1 << 20], "bf16")
     assert np.array_equal(got, ref_bits)
     st.close()
-    # (kind, store hook, tolerance).  Against the exact oracle the 7B layer meets 1e-2.  For the 70B shard
-    # (hidden 8192) rounding every stored tensor to bf16 ALONE moves dX by 1.2e-2 from the exact result
-    # (oracle's storage-rounded mode vs its exact mode), so the exact distance is bounded by 2e-2 there and the
-    # sharp check is the one against the storage-rounded mode.
-    exact_tol = 1e-2 if name == "7b" else 2e-2
+    # (kind, store hook, tolerance).  Against the exact oracle the 7B layer meets 1e-2.  For the wider layers rounding
+    # every stored tensor to bf16 ALONE moves the result past 1e-2 from the exact one (oracle's storage-rounded mode
+    # vs its exact mode: dX by 1.2e-2 for the 70B shard, hidden 8192; the QKV-side gradients by about 1e-2 for 13B,
+    # hidden 5120), so the exact distance is bounded by 1.5e-2 / 2e-2 there and the sharp check is the one against the
+    # storage-rounded mode.
+    exact_tol = {"7b": 1e-2, "13b": 1.5e-2, "70b_tp4": 2e-2}[name]
     for kind, store, tol in (("exact", None, exact_tol), ("stored", bf16_store, 1e-2)):
         t0 = time.time()
         rys, rdxs, rg = oracle_step(sh, 1001, 2001, 3001, [1], params64=p64, store=store)
