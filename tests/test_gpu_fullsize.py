@@ -40,3 +40,55 @@ def test_full_shape_single_layer(name):
         print(f"[{name}] vs {kind} oracle ({time.time() - t0:.1f} s): y={ey:.2e} dx={ex:.2e} grads(max)={eg:.2e}", flush=True)
         assert ey <= tol and ex <= tol, (kind, ey, ex)
         assert eg <= tol, (kind, sorted(errs.items(), key=lambda kv: -kv[1])[:3])
+
+
+@pytest.mark.timeout(600)
+def test_headline_configuration_four_layers_four_microbatches():
+    """The benchmark's own launch configuration (7B shape, 4 layers, 4 micro-batches, one backward call in overwrite
+    mode).  Properties at full size: y and dX of every micro-batch are bitwise what a one-at-a-time execution gives
+    and the batched weight gradient equals the sum of the four single ones to fp32 summation order.  Parity at full
+    depth: micro-batch 0 through all four layers against the oracle in storage-rounded mode (y, dX, and the
+    gradients of a run that holds only micro-batch 0).  The 1e-2 bound is a one-layer bound: bf16 storage noise grows
+    with depth, and the oracle's own storage-rounded mode stands 1.04e-2 (y), 1.41e-2 (dX) and 2.63e-2 (largest
+    gradient distance, gamma1 / w_qkv of the last layer) from its exact mode on these very inputs (measured on the
+    CPU, oracle only).  Two bf16 executions that round in different orders sit at that distance from each other
+    too, so the bounds here are 1.5 times those floors."""
+    import torch
+    import paper_2410_13333_amd as mls
+    from tests.helpers import to_device, to_host64
+    sh = synth.CONFIGS["7b"]
+    K, M = sh.layers, sh.microbatches
+    st = mls.Stage.from_shape(sh, seed=1001)
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    xs = [to_device(synth.make_x(sh, 2001, mb)[0], "bf16") for mb in range(M)]
+    dy = torch.stack([to_device(synth.make_dy(sh, 3001, mb)[0], "bf16") for mb in range(M)])
+    ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(M)]
+    dx = torch.empty_like(dy)
+    grads = torch.full((st.grad_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    for mb in range(M):
+        st.forward(xs[mb], K, ys[mb])
+    st.backward(dy, grads, M, dx, overwrite=True)
+    torch.cuda.synchronize()
+    # one at a time
+    y1, dx1 = torch.empty_like(ys[0]), torch.empty_like(dy[:1])
+    gsum = torch.zeros_like(grads)
+    g0 = None
+    for mb in range(M):
+        g1 = torch.empty_like(grads)
+        st.forward(xs[mb], K, y1)
+        st.backward(dy[mb:mb + 1], g1, 1, dx1, overwrite=True)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, ys[mb]) and torch.equal(dx1[0], dx[mb])
+        gsum += g1
+        if mb == 0:
+            g0 = to_host64(g1)
+    assert rel_err(to_host64(grads), to_host64(gsum)) < 1e-6
+    del gsum, g1
+    y0, dx0 = to_host64(ys[0]), to_host64(dx[0])
+    st.close()
+    t0 = time.time()
+    rys, rdxs, rg = oracle_step(sh.with_(microbatches=1), 1001, 2001, 3001, [K], store=bf16_store)
+    ey, ex = rel_err(y0, rys[0]), rel_err(dx0, rdxs[0])
+    eg, errs = grad_errors(sh, g0, rg, K)
+    print(f"[7b 4 layers] vs stored oracle ({time.time() - t0:.1f} s): y={ey:.2e} dx={ex:.2e} grads(max)={eg:.2e}", flush=True)
+    assert ey <= 1.6e-2 and ex <= 2.1e-2 and eg <= 4e-2, (ey, ex, sorted(errs.items(), key=lambda kv: -kv[1])[:3])
