@@ -70,8 +70,8 @@ enum {
   MLS_T_GU = 6,   /* gate|up                  [T, 2*ffn]                                    */
   MLS_T_Z = 7,    /* SwiGLU output            [T, ffn]                                      */
   MLS_T_LSE = 8,  /* natural-log softmax denominators, fp32 [micro_batch, n_q_heads, seq]   */
-  /* the upstream-gradient operands of the LAST (layer, micro-batch) pair processed by the most recent backward
-     call, i.e. layer 0 of its last micro-batch (workspace, overwritten by later calls): */
+  /* the upstream-gradient operands of layer 0 of one micro-batch of the most recent backward call (workspace,
+     overwritten by later calls); `slot` is the index of the micro-batch inside that call: */
   MLS_T_DY = 16,   /* gradient w.r.t. the layer output   [T, hidden]                        */
   MLS_T_DGU = 17,  /* gradient w.r.t. gate|up            [T, 2*ffn]                         */
   MLS_T_DH = 18,   /* gradient w.r.t. h                  [T, hidden]                        */
@@ -172,8 +172,9 @@ int mls_stage_reset(mls_stage* s);
 
 /* Operand capture for tests: copy tensor `tensor_id` (MLS_T_*) of `layer` of the stash entry that is
  * `slot` pushes old (0 = oldest) into the DEVICE buffer dst, which must hold the tensor (with recomputation
- * only MLS_T_X is kept: the other stash tensors give MLS_E_RANGE).  For MLS_T_D*
- * ids `layer` and `slot` are ignored.  Errors: MLS_E_NULL, MLS_E_RANGE, MLS_E_HIP. */
+ * only MLS_T_X is kept: the other stash tensors give MLS_E_RANGE).  For the MLS_T_D* ids `layer` is ignored
+ * (always layer 0) and `slot` counts the micro-batches of the most recent backward call (0 = its first; an
+ * entry that ran no layer gives MLS_E_RANGE).  Errors: MLS_E_NULL, MLS_E_RANGE, MLS_E_HIP. */
 int mls_stage_debug_read(mls_stage* s, int32_t tensor_id, int32_t layer, int32_t slot, void* dst);
 
 /* Per-kernel-class timing with HIP events recorded on the stage's stream, for the benchmark's roofline figure.

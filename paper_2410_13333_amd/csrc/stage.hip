@@ -109,9 +109,7 @@ struct mls_stage {
        *dqkv = nullptr;
   size_t mb_h = 0, mb_gu = 0, mb_qkv = 0;  // bytes per micro-batch of the [T,ld_h], [T,ld_gu], [T,ld_qkv] buffers
   float *delta = nullptr, *partial = nullptr, *gqa_part = nullptr;  // gqa_part: partial dK/dV sums (few KV heads)
-  const void* last_dy = nullptr;
-  int64_t last_dy_ld = 0;
-  int last_ws = 0;  // micro-batch workspace used by the most recent layer backward
+  std::vector<int> last_k;  // layer counts of the entries of the most recent backward call (for mls_stage_debug_read)
   Timing tm;
 
   char* slot_layer(int slot, int layer) const {
@@ -487,9 +485,6 @@ int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n,
       }
       const char* dy = pp(i, (l + 1) & 1);
       void* dx = l == 0 ? (void*)((char*)dX + size_t(i) * act) : (void*)pp(i, l & 1);
-      s->last_dy = dy;
-      s->last_dy_ld = s->ld_h;
-      s->last_ws = i;
       if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g, ow && az.empty())) return rc;
       az.push_back(e + L.z); ab.push_back(e + L.b); ao.push_back(e + L.o); aa.push_back(e + L.a);
       bdy.push_back(dy);
@@ -508,6 +503,7 @@ int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n,
     HIP_TRY(mls::fill_zero_f32(grads + size_t(kmax) * s->layer_params, size_t(c.max_layers - kmax) * s->layer_params, s->st));
   s->head = (s->head + n) % c.max_inflight;
   s->count -= n;
+  s->last_k = k;
   return MLS_OK;
 }
 
@@ -602,14 +598,17 @@ int mls_stage_debug_read(mls_stage* s, int32_t id, int32_t layer, int32_t slot, 
   const void* src = nullptr;
   int64_t cols = 0, ld = 0;
   if (id >= MLS_T_DY) {
+    // layer 0 of micro-batch `slot` of the most recent backward call: its workspace entries are still intact,
+    // and the gradient w.r.t. the output of layer 0 sits in ping-pong buffer 1
+    if (slot < 0 || slot >= (int)s->last_k.size()) return fail(MLS_E_RANGE, "micro-batch index beyond the most recent backward call");
+    if (s->last_k[slot] == 0) return fail(MLS_E_RANGE, "that micro-batch ran no layer");
     switch (id) {
-      case MLS_T_DY: src = s->last_dy; cols = h; ld = s->last_dy_ld; break;
-      case MLS_T_DGU: src = s->dgu + size_t(s->last_ws) * s->mb_gu; cols = 2 * f; ld = s->ld_gu; break;
-      case MLS_T_DH: src = s->dh + size_t(s->last_ws) * s->mb_h; cols = h; ld = s->ld_h; break;
-      case MLS_T_DQKV: src = s->dqkv + size_t(s->last_ws) * s->mb_qkv; cols = s->qkvw; ld = s->ld_qkv; break;
+      case MLS_T_DY: src = s->g1 + size_t(slot) * s->mb_h; cols = h; ld = s->ld_h; break;
+      case MLS_T_DGU: src = s->dgu + size_t(slot) * s->mb_gu; cols = 2 * f; ld = s->ld_gu; break;
+      case MLS_T_DH: src = s->dh + size_t(slot) * s->mb_h; cols = h; ld = s->ld_h; break;
+      case MLS_T_DQKV: src = s->dqkv + size_t(slot) * s->mb_qkv; cols = s->qkvw; ld = s->ld_qkv; break;
       default: return fail(MLS_E_RANGE, "unknown tensor id");
     }
-    if (!s->last_dy) return fail(MLS_E_RANGE, "no backward has run yet");
   } else {
     if (slot < 0 || slot >= s->count) return fail(MLS_E_RANGE, "stash slot out of range");
     const int phys = (s->head + slot) % s->c.max_inflight;

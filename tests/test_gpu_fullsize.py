@@ -45,7 +45,8 @@ def test_full_shape_single_layer(name):
 @pytest.mark.timeout(600)
 def test_headline_configuration_four_layers_four_microbatches():
     """The benchmark's own launch configuration (7B shape, 4 layers, 4 micro-batches, one backward call in overwrite
-    mode).  Properties at full size: y and dX of every micro-batch are bitwise what a one-at-a-time execution gives
+    mode).  The weight gradients of layer 0, sampled, against fp64 sums over the captured bf16 operands of all four
+    micro-batches (1e-4).  Properties at full size: y and dX of every micro-batch are bitwise what a one-at-a-time execution gives
     and the batched weight gradient equals the sum of the four single ones to fp32 summation order.  Parity at full
     depth: micro-batch 0 through all four layers against the oracle in storage-rounded mode (y, dX, and the
     gradients of a run that holds only micro-batch 0).  The 1e-2 bound is a one-layer bound: bf16 storage noise grows
@@ -67,8 +68,31 @@ def test_headline_configuration_four_layers_four_microbatches():
     grads = torch.full((st.grad_elems,), float("nan"), dtype=torch.float32, device="cuda")
     for mb in range(M):
         st.forward(xs[mb], K, ys[mb])
+    # operand capture (layer 0): sampled rows of the weight = sampled columns of its activation operand
+    pairs = (("w_d", "z", "dy"), ("w_gu", "b", "dgu"), ("w_o", "o", "dh"), ("w_qkv", "a", "dqkv"))
+    rng = np.random.default_rng(7)
+
+    def pick(n):  # both ends (the last columns belong to the narrower tail tiles) and a random spread
+        return np.unique(np.concatenate([np.arange(8), np.arange(n - 8, n), rng.integers(0, n, 48)]))
+    sel = {}
+    for w, _, _ in pairs:
+        _, rows, cols = st.param_layout(0, w)
+        sel[w] = (pick(rows), pick(cols))
+    act = {w: [to_host64(st.debug_read(a, 0, mb)[:, torch.from_numpy(sel[w][0]).cuda()]) for mb in range(M)] for w, a, _ in pairs}
     st.backward(dy, grads, M, dx, overwrite=True)
     torch.cuda.synchronize()
+    # the 1e-4 bar of the fp32-accumulated weight gradients at full size, all four micro-batches in one call:
+    # sampled entries rebuilt in fp64 from exactly the captured bf16 operands
+    gl0 = grads[:st.grad_elems // st.cfg.max_layers]
+    for w, _, b in pairs:
+        off, rows, cols = st.param_layout(0, w)
+        R, Cc = sel[w]
+        ref = sum(act[w][mb].T @ to_host64(st.debug_read(b, 0, mb)[:, torch.from_numpy(Cc).cuda()]) for mb in range(M))
+        got = to_host64(gl0[off:off + rows * cols].reshape(rows, cols)[torch.from_numpy(R).cuda()][:, torch.from_numpy(Cc).cuda()])
+        e = rel_err(got, ref)
+        print(f"[7b 4x4] {w} sampled {len(R)}x{len(Cc)} entries vs fp64 from captured operands: {e:.2e}", flush=True)
+        assert e <= 1e-4, (w, e)
+    del act
     # one at a time
     y1, dx1 = torch.empty_like(ys[0]), torch.empty_like(dy[:1])
     gsum = torch.zeros_like(grads)

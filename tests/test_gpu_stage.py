@@ -174,29 +174,41 @@ def test_zero_layers_zero_microbatches_and_errors():
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("batched", [False, True])
 @pytest.mark.parametrize("base", ["ragged", "fused"])
-def test_weight_gradient_contraction_given_identical_operands_1e4(base):
+def test_weight_gradient_contraction_given_identical_operands_1e4(base, batched):
     """The 1e-4 bar of the fp32-accumulated weight gradients: capture the bf16 operand pairs of every
-    weight-gradient contraction of layer 0 and rebuild sum_mb X^T dY in fp64 from exactly those operands."""
+    weight-gradient contraction of layer 0 and rebuild sum_mb X^T dY in fp64 from exactly those operands.
+    batched: all micro-batches go through ONE backward call (one contraction per weight over all of them, in a
+    two-layer stage); otherwise one call per micro-batch accumulates into the same gradient vector."""
     import torch
     import paper_2410_13333_amd as mls
-    sh = (RAGGED if base == "ragged" else FUSED_RAGGED).with_(layers=1)
-    n = 3
-    st = mls.Stage.from_shape(sh, seed=1000, max_inflight=1)
+    sh = (RAGGED if base == "ragged" else FUSED_RAGGED).with_(layers=2 if batched else 1)
+    n, K = 3, sh.layers
+    st = mls.Stage.from_shape(sh, seed=1000, max_inflight=n if batched else 1)
     g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
     ref = {k: 0.0 for k in ("w_d", "w_gu", "w_o", "w_qkv")}
-    for mb in range(n):
-        x = to_device(synth.make_x(sh, 2000, mb)[0], "bf16")
-        dy = to_device(synth.make_dy(sh, 3000, mb)[0], "bf16")[None]
-        y, dx = torch.empty_like(x), torch.empty_like(dy)
-        st.forward(x, 1, y)
-        ops = {k: to_host64(st.debug_read(k)) for k in ("z", "b", "o", "a")}
-        st.backward(dy, g, 1, dx)
-        ups = {k: to_host64(st.debug_read(k)) for k in ("dy", "dgu", "dh", "dqkv")}
-        ref["w_d"] = ref["w_d"] + ops["z"].T @ ups["dy"]
-        ref["w_gu"] = ref["w_gu"] + ops["b"].T @ ups["dgu"]
-        ref["w_o"] = ref["w_o"] + ops["o"].T @ ups["dh"]
-        ref["w_qkv"] = ref["w_qkv"] + ops["a"].T @ ups["dqkv"]
+    pairs = (("w_d", "z", "dy"), ("w_gu", "b", "dgu"), ("w_o", "o", "dh"), ("w_qkv", "a", "dqkv"))
+    xs = [to_device(synth.make_x(sh, 2000, mb)[0], "bf16") for mb in range(n)]
+    dys = torch.stack([to_device(synth.make_dy(sh, 3000, mb)[0], "bf16") for mb in range(n)])
+    y, dx = torch.empty_like(xs[0]), torch.empty_like(dys)
+    if batched:
+        for mb in range(n):
+            st.forward(xs[mb], K, y)
+        ops = [{k: to_host64(st.debug_read(k, 0, mb)) for _, k, _ in pairs} for mb in range(n)]
+        st.backward(dys, g, n, dx)
+        for mb in range(n):
+            for w, a, b in pairs:
+                ref[w] = ref[w] + ops[mb][a].T @ to_host64(st.debug_read(b, 0, mb))
+        with pytest.raises(mls.MlsError):
+            st.debug_read("dy", 0, n)  # beyond the micro-batches of that call
+    else:
+        for mb in range(n):
+            st.forward(xs[mb], K, y)
+            ops = {k: to_host64(st.debug_read(k)) for _, k, _ in pairs}
+            st.backward(dys[mb:mb + 1], g, 1, dx[mb:mb + 1])
+            for w, a, b in pairs:
+                ref[w] = ref[w] + ops[a].T @ to_host64(st.debug_read(b))
     torch.cuda.synchronize()
     gh = to_host64(g)
     for name, r in ref.items():
