@@ -42,22 +42,25 @@ def test_full_shape_single_layer(name):
         assert eg <= tol, (kind, sorted(errs.items(), key=lambda kv: -kv[1])[:3])
 
 
+@pytest.mark.parametrize("name", ["7b", "13b", "70b_tp4"])
 @pytest.mark.timeout(600)
-def test_headline_configuration_four_layers_four_microbatches():
-    """The benchmark's own launch configuration (7B shape, 4 layers, 4 micro-batches, one backward call in overwrite
-    mode).  The weight gradients of layer 0, sampled, against fp64 sums over the captured bf16 operands of all four
-    micro-batches (1e-4).  Properties at full size: y and dX of every micro-batch are bitwise what a one-at-a-time execution gives
-    and the batched weight gradient equals the sum of the four single ones to fp32 summation order.  Parity at full
-    depth: micro-batch 0 through all four layers against the oracle in storage-rounded mode (y, dX, and the
-    gradients of a run that holds only micro-batch 0).  The 1e-2 bound is a one-layer bound: bf16 storage noise grows
-    with depth, and the oracle's own storage-rounded mode stands 1.04e-2 (y), 1.41e-2 (dX) and 2.63e-2 (largest
-    gradient distance, gamma1 / w_qkv of the last layer) from its exact mode on these very inputs (measured on the
-    CPU, oracle only).  Two bf16 executions that round in different orders sit at that distance from each other
-    too, so the bounds here are 1.5 times those floors."""
+def test_full_configuration_all_layers_all_microbatches(name):
+    """The benchmark's own launch configurations (7B: 4 layers x 4 micro-batches; 13B: 5 x 7; 70B shard: 3 x 8), one
+    backward call in overwrite mode.
+    (1) The weight gradients of layer 0, sampled, against fp64 sums over the captured bf16 operands of all the
+    micro-batches: 1e-4.
+    (2) Properties that hold at any size: y and dX of every micro-batch are bitwise what a one-at-a-time execution
+    gives, and the batched weight gradient equals the sum of the single ones to fp32 summation order.
+    (3) Parity at full depth (7B only: the oracle needs a minute for it): micro-batch 0 through all four layers
+    against the oracle in storage-rounded mode (y, dX, and the gradients of a run that holds only micro-batch 0).
+    The 1e-2 bound is a one-layer bound: bf16 storage noise grows with depth, and the oracle's own storage-rounded
+    mode stands 1.04e-2 (y), 1.41e-2 (dX) and 2.63e-2 (largest gradient distance, gamma1 / w_qkv of the last layer)
+    from its exact mode on these very inputs (measured on the CPU, oracle only).  Two bf16 executions that round
+    in different orders sit at that distance from each other too, so the bounds here are 1.5 times those floors."""
     import torch
     import paper_2410_13333_amd as mls
     from tests.helpers import to_device, to_host64
-    sh = synth.CONFIGS["7b"]
+    sh = synth.CONFIGS[name]
     K, M = sh.layers, sh.microbatches
     st = mls.Stage.from_shape(sh, seed=1001)
     shape = (sh.micro_batch, sh.seq, sh.hidden)
@@ -81,7 +84,7 @@ def test_headline_configuration_four_layers_four_microbatches():
     act = {w: [to_host64(st.debug_read(a, 0, mb)[:, torch.from_numpy(sel[w][0]).cuda()]) for mb in range(M)] for w, a, _ in pairs}
     st.backward(dy, grads, M, dx, overwrite=True)
     torch.cuda.synchronize()
-    # the 1e-4 bar of the fp32-accumulated weight gradients at full size, all four micro-batches in one call:
+    # the 1e-4 bar of the fp32-accumulated weight gradients at full size, all micro-batches in one call:
     # sampled entries rebuilt in fp64 from exactly the captured bf16 operands
     gl0 = grads[:st.grad_elems // st.cfg.max_layers]
     for w, _, b in pairs:
@@ -90,7 +93,7 @@ def test_headline_configuration_four_layers_four_microbatches():
         ref = sum(act[w][mb].T @ to_host64(st.debug_read(b, 0, mb)[:, torch.from_numpy(Cc).cuda()]) for mb in range(M))
         got = to_host64(gl0[off:off + rows * cols].reshape(rows, cols)[torch.from_numpy(R).cuda()][:, torch.from_numpy(Cc).cuda()])
         e = rel_err(got, ref)
-        print(f"[7b 4x4] {w} sampled {len(R)}x{len(Cc)} entries vs fp64 from captured operands: {e:.2e}", flush=True)
+        print(f"[{name} {K}x{M}] {w} sampled {len(R)}x{len(Cc)} entries vs fp64 from captured operands: {e:.2e}", flush=True)
         assert e <= 1e-4, (w, e)
     del act
     # one at a time
@@ -106,10 +109,13 @@ def test_headline_configuration_four_layers_four_microbatches():
         gsum += g1
         if mb == 0:
             g0 = to_host64(g1)
-    assert rel_err(to_host64(grads), to_host64(gsum)) < 1e-6
+    # the orders differ (one register accumulation over M*T terms vs M rounded fp32 sums): about 1e-6 at M = 7, 8
+    assert rel_err(to_host64(grads), to_host64(gsum)) < 1e-5
     del gsum, g1
     y0, dx0 = to_host64(ys[0]), to_host64(dx[0])
     st.close()
+    if name != "7b":
+        return
     t0 = time.time()
     rys, rdxs, rg = oracle_step(sh.with_(microbatches=1), 1001, 2001, 3001, [K], store=bf16_store)
     ey, ex = rel_err(y0, rys[0]), rel_err(dx0, rdxs[0])
