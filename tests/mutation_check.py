@@ -96,7 +96,7 @@ def main():
     survivors = []
     with tempfile.TemporaryDirectory() as tmp:
         for name in os.listdir(ROOT):
-            if name in ("oracle", "_work", "gpurun_out", ".git") or name.startswith("."):
+            if name == "oracle" or name.startswith((".", "_")) or not (name.endswith(".py") or os.path.isdir(os.path.join(ROOT, name))):
                 continue
             os.symlink(os.path.join(ROOT, name), os.path.join(tmp, name))
         os.mkdir(os.path.join(tmp, "oracle"))

@@ -1,5 +1,5 @@
 """1F1B-ordered execution with stash accounting, activation recomputation, and the memory report against the
-device (SURVEY's next row after the stage itself; Appendix B.4 of the paper for the memory model).
+device (Appendix B.4 of the paper for the memory model).
 
 Recomputation runs the same kernels on the same inputs, so its results must equal the kept-activation results
 bit for bit; a 1F1B order pops the same entries one at a time, so y and dX are bitwise equal to the
@@ -102,3 +102,62 @@ def test_memory_report_matches_the_device(recompute):
     used = free0 - free1
     st.close()
     assert want <= used <= want * 1.01 + 64 * 2 ** 20, (want, used)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_stage_step_replays_from_a_hip_graph(dtype):
+    """A whole stage step (forwards with different layer counts, one backward) captured into a HIP graph on the
+    stage's stream replays bit for bit: the library allocates nothing, synchronises nothing and records no memset on
+    the hot path, and the stash ring returns to its starting slot after a step that fills it.  Replays alternate
+    with eager steps on other inputs and with synchronisations; every replay is compared with the eager result."""
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = synth.StageShape(hidden=192, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=352, seq=200, micro_batch=2,
+                          layers=3, microbatches=3, dtype=dtype)
+    ks = [3, 1, 2]
+    side = torch.cuda.Stream()
+    st = mls.Stage.from_shape(sh, seed=1000, stream=side)
+    M = len(ks)
+    shape = (sh.micro_batch, sh.seq, sh.hidden)
+    xs = [to_device(synth.make_x(sh, 2000, mb)[0], dtype) for mb in range(M)]
+    other = [to_device(synth.make_x(sh, 2100, mb)[0], dtype) for mb in range(M)]
+    dy = torch.stack([to_device(synth.make_dy(sh, 3000, mb)[0], dtype) for mb in range(M)])
+    xin = [x.clone() for x in xs]  # the graph reads these buffers; their contents may change between replays
+    ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(M)]
+    dx = torch.empty_like(dy)
+    grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+
+    def step():
+        for mb in range(M):
+            st.forward(xin[mb], ks[mb], ys[mb])
+        st.backward(dy, grads, M, dx, overwrite=True)
+
+    def run_eager():
+        with torch.cuda.stream(side):
+            step()
+        side.synchronize()
+        return [y.clone() for y in ys], dx.clone(), grads.clone()
+    torch.cuda.synchronize()
+    ref = run_eager()                      # also the warm-up that sets the kernels' attributes
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(3):
+        for a, b in zip(xin, other):       # eager work on other inputs between the replays
+            a.copy_(b)
+        torch.cuda.synchronize()
+        got_other = run_eager()
+        assert not torch.equal(got_other[1], ref[1])
+        for a, b in zip(xin, xs):
+            a.copy_(b)
+        grads.fill_(float("nan"))
+        dx.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(ys, ref[0])), rep
+        assert torch.equal(dx, ref[1]) and torch.equal(grads, ref[2]), rep
+    assert st.inflight == 0
+    del graph
+    st.close()
