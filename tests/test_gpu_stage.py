@@ -264,3 +264,15 @@ def test_overwrite_mode_equals_zeroing_then_accumulating(base):
     torch.cuda.synchronize()
     assert not to_host64(grads).any()
     st.close()
+
+
+@pytest.mark.parametrize("seq,mb", [(37, 1), (1, 1), (3, 3), (65, 2)])
+def test_token_counts_that_are_not_multiples_of_eight(seq, mb):
+    """Tokens per micro-batch T = seq * micro_batch need not be a multiple of anything: T is the row count of
+    every activation and the contraction length of the weight gradients (zero-filled beyond the last row).
+    seq = 1: attention over a single position is the identity on v."""
+    for ffn in (40, 64):  # separate and fused SwiGLU
+        sh = synth.StageShape(hidden=72, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=ffn, seq=seq, micro_batch=mb,
+                              layers=2, microbatches=2)
+        _check(sh, [2, 1], 1e-2)
+    _check(sh.with_(dtype="fp32", head_dim=16), [2, 1], 1e-4)
