@@ -178,13 +178,8 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
                   int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st) {
   using G = Geo<BM, BN, BK, WGM, WGN, ATR, BTR>;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, ATR, BTR, EPI>;
-  static bool attr_set = false;  // raising the dynamic LDS limit is a per-function, once-only call
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)G::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};
+  if (hipError_t e = mls::raise_lds_limit(reinterpret_cast<const void*>(kern), (int)G::LDS_BYTES, lds_raised)) return e;
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(G::NT), G::LDS_BYTES, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, tm, tn);
   return hipGetLastError();

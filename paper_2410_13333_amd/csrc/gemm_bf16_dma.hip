@@ -416,12 +416,8 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};
+  if (hipError_t e = mls::raise_lds_limit(reinterpret_cast<const void*>(kern), LDS, lds_raised)) return e;
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(NW * 64), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm,
                      col0, X, ldx, xf, sa);

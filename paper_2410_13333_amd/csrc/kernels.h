@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace mls {
 
 enum { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
@@ -11,6 +13,19 @@ enum { DT_BF16 = 0, DT_FP32 = 1 };
 
 // records `msg` as the calling thread's mls_last_error text and returns `code` (stage.hip)
 int set_error(int code, const char* msg);
+
+// Raises a kernel's dynamic-LDS limit, once per device (the attribute belongs to the function on the current
+// device).  `done` is the launcher's own bit mask of devices already served; racing threads at worst set it twice.
+inline hipError_t raise_lds_limit(const void* kern, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = uint64_t(1) << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // ---- contractions (gemm_bf16.hip, gemm_f32.hip); modes as documented at mls_gemm; leading dims in elements
 // (ldr: row stride of the residual R, ignored when R is null)
