@@ -459,13 +459,12 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
   // 128x64 each: the second wavefront covers the first one's barrier and load waits; forward -5 %, data gradient
   // -3 %), the fp32 read-modify-write mode runs 4 (128x128 each; 8 measured 2.5 % slower there).
   constexpr bool nw8 = EPI != EPI_F32_ACC;
+  constexpr int NW = nw8 ? 8 : 4;
   if (big_tiles >= 192) {
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
-      hipError_t e = nw8 ? launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, 8>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
-                                                                    nullptr, 0, x.X, x.ldx, x.xf)
-                         : launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
-                                                                    nullptr, 0, x.X, x.ldx, x.xf);
+      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
+                                                                             nullptr, 0, x.X, x.ldx, x.xf);
       if (e != hipSuccess) return e;
       // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
       const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
@@ -473,10 +472,8 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
       return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st,
                                                             nullptr, n1, x.X, x.ldx, x.xf);
     }
-    if (nw8) return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, 8>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
-                                                          x.X, x.ldx, x.xf);
-    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
-                                                          x.X, x.ldx, x.xf);
+    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
+                                                                   x.X, x.ldx, x.xf);
   }
   return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0, x.X,
                                                  x.ldx, x.xf);
