@@ -46,6 +46,22 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_fwd_kernel(const T* __rest
   }
 }
 
+// eight consecutive bf16 elements as they lie in memory (16 bytes), converted on demand
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<bf16_t> {
+  uint4 v;
+  __device__ __forceinline__ void load(const bf16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void get(float (&o)[8]) const {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      o[2 * i] = __uint_as_float(w[i] << 16);
+      o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
 // ---------------------------------------------------------------- RMSNorm backward
 // Workgroup w handles rows w, w + gridDim.x, ...; it keeps its share of the column sums for dgamma in
 // registers and writes them to partial[w][:], which a second kernel adds up in a fixed order.
@@ -66,48 +82,106 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
     for (int e = 0; e < 8; e++) dg[i][e] = 0.f;
     if (c < nchunk) load8(gamma + c * 8, g[i]);
   }
-  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
-    const float r = rstd[row];
-    float n[NORM_MAXC][8], dn[NORM_MAXC][8];
-    float dot = 0.f;
+  // bf16 rows of up to 8192 elements are software-pipelined: the (unconverted) operands of the workgroup's next
+  // row are requested before the current row is reduced, so that two rows per workgroup are in flight.  Wider or
+  // fp32 rows would not fit the registers that way and take the plain loop.
+  if constexpr (sizeof(T) == 2 && NORM_MAXC <= 4) {
+    Raw8<T> rx[NORM_MAXC], rda[NORM_MAXC], rres[NORM_MAXC];
+    auto request = [&](int64_t row) {
 #pragma unroll
-    for (int i = 0; i < NORM_MAXC; i++) {
-      const int c = threadIdx.x + i * EW_THREADS;
-      if (c < nchunk) {
-        float xv[8], dav[8];
-        load8(x + row * ldx + c * 8, xv);
-        load8(da + row * ld_da + c * 8, dav);
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          rx[i].load(x + row * ldx + c * 8);
+          rda[i].load(da + row * ld_da + c * 8);
+          if (dres) rres[i].load(dres + row * ld_dres + c * 8);
+        }
+      }
+    };
+    if (blockIdx.x < rows) request(blockIdx.x);
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+      const float r = rstd[row];
+      float n[NORM_MAXC][8], dn[NORM_MAXC][8], res[NORM_MAXC][8];
+      float dot = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-          n[i][e] = xv[e] * r;
-          dn[i][e] = dav[e] * g[i][e];
-          dg[i][e] += dav[e] * n[i][e];
-          dot += dn[i][e] * n[i][e];
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          float xv[8], dav[8];
+          rx[i].get(xv);
+          rda[i].get(dav);
+          if (dres) {
+            rres[i].get(res[i]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; e++) res[i][e] = 0.f;
+          }
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            n[i][e] = xv[e] * r;
+            dn[i][e] = dav[e] * g[i][e];
+            dg[i][e] += dav[e] * n[i][e];
+            dot += dn[i][e] * n[i][e];
+          }
+        }
+      }
+      if (row + gridDim.x < rows) request(row + gridDim.x);
+      const float mean = block_sum(dot, red) / (float)h;
+#pragma unroll
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          float o[8];
+#pragma unroll
+          for (int e = 0; e < 8; e++) o[e] = res[i][e] + r * (dn[i][e] - n[i][e] * mean);
+          store8(dx + row * ld_dx + c * 8, o);
         }
       }
     }
-    float res[NORM_MAXC][8];  // requested before the reduction so that their latency overlaps it
+  } else {
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+      const float r = rstd[row];
+      float n[NORM_MAXC][8], dn[NORM_MAXC][8];
+      float dot = 0.f;
 #pragma unroll
-    for (int i = 0; i < NORM_MAXC; i++) {
-      const int c = threadIdx.x + i * EW_THREADS;
-      if (c < nchunk) {
-        if (dres) {
-          load8(dres + row * ld_dres + c * 8, res[i]);
-        } else {
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          float xv[8], dav[8];
+          load8(x + row * ldx + c * 8, xv);
+          load8(da + row * ld_da + c * 8, dav);
 #pragma unroll
-          for (int e = 0; e < 8; e++) res[i][e] = 0.f;
+          for (int e = 0; e < 8; e++) {
+            n[i][e] = xv[e] * r;
+            dn[i][e] = dav[e] * g[i][e];
+            dg[i][e] += dav[e] * n[i][e];
+            dot += dn[i][e] * n[i][e];
+          }
         }
       }
-    }
-    const float mean = block_sum(dot, red) / (float)h;
+      float res[NORM_MAXC][8];  // requested before the reduction so that their latency overlaps it
 #pragma unroll
-    for (int i = 0; i < NORM_MAXC; i++) {
-      const int c = threadIdx.x + i * EW_THREADS;
-      if (c < nchunk) {
-        float o[8];
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          if (dres) {
+            load8(dres + row * ld_dres + c * 8, res[i]);
+          } else {
 #pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = res[i][e] + r * (dn[i][e] - n[i][e] * mean);
-        store8(dx + row * ld_dx + c * 8, o);
+            for (int e = 0; e < 8; e++) res[i][e] = 0.f;
+          }
+        }
+      }
+      const float mean = block_sum(dot, red) / (float)h;
+#pragma unroll
+      for (int i = 0; i < NORM_MAXC; i++) {
+        const int c = threadIdx.x + i * EW_THREADS;
+        if (c < nchunk) {
+          float o[8];
+#pragma unroll
+          for (int e = 0; e < 8; e++) o[e] = res[i][e] + r * (dn[i][e] - n[i][e] * mean);
+          store8(dx + row * ld_dx + c * 8, o);
+        }
       }
     }
   }
