@@ -71,7 +71,8 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
                                                                  const T* __restrict__ gamma,
                                                                  const float* __restrict__ rstd, const T* dres,
                                                                  int64_t ld_dres, T* dx, int64_t ld_dx,
-                                                                 float* __restrict__ partial, int rows, int h) {
+                                                                 float* __restrict__ partial, int rows, int h,
+                                                                 bool acc_partial) {
   __shared__ float red[EW_THREADS / 64];
   const int nchunk = h >> 3;
   float g[NORM_MAXC][8], dg[NORM_MAXC][8];
@@ -188,7 +189,16 @@ __global__ __launch_bounds__(EW_THREADS) void rmsnorm_bwd_kernel(const T* __rest
 #pragma unroll
   for (int i = 0; i < NORM_MAXC; i++) {
     const int c = threadIdx.x + i * EW_THREADS;
-    if (c < nchunk) store8(partial + int64_t(blockIdx.x) * h + c * 8, dg[i]);
+    if (c < nchunk) {
+      float* p = partial + int64_t(blockIdx.x) * h + c * 8;
+      if (acc_partial) {  // on top of what earlier calls left (same workgroup, same rows' share: a fixed order)
+        float prev[8];
+        load8(p, prev);
+#pragma unroll
+        for (int e = 0; e < 8; e++) dg[i][e] += prev[e];
+      }
+      store8(p, dg[i]);
+    }
   }
 }
 
@@ -367,12 +377,12 @@ int rmsnorm_bwd_blocks(int T) { return T < 512 ? (T > 0 ? T : 1) : 512; }
 
 hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
                        const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
-                       float* partial, int T, int h, hipStream_t st, bool overwrite) {
+                       float* partial, int T, int h, hipStream_t st, bool overwrite, bool acc_partial, bool reduce) {
   if (T == 0) return hipSuccess;
   const int nb = rmsnorm_bwd_blocks(T);
 #define BWD(TY, C)                                                                                               \
   hipLaunchKernelGGL((rmsnorm_bwd_kernel<TY, C>), dim3(nb), dim3(EW_THREADS), 0, st, (const TY*)da, ld_da,            \
-                     (const TY*)x, ldx, (const TY*)gamma, r, (const TY*)dres, ld_dres, (TY*)dx, ld_dx, partial, T, h)
+                     (const TY*)x, ldx, (const TY*)gamma, r, (const TY*)dres, ld_dres, (TY*)dx, ld_dx, partial, T, h, acc_partial)
   const int mc = h <= 4096 ? 2 : h <= 8192 ? 4 : 8;
   if (dt == DT_BF16) {
     if (mc == 2) BWD(bf16_t, 2); else if (mc == 4) BWD(bf16_t, 4); else BWD(bf16_t, 8);
@@ -381,7 +391,7 @@ hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int
   }
 #undef BWD
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !reduce) return e;
   hipLaunchKernelGGL(colsum_add_kernel, dim3((h + 15) / 16), dim3(256), 0, st, partial, dgamma, nb, h, overwrite);
   return hipGetLastError();
 }

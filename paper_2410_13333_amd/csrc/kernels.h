@@ -61,11 +61,14 @@ hipError_t rmsnorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, vo
                        int h, float eps, hipStream_t st);
 // dx = dres + r*(dn - n*mean(dn*n)), dn = da*gamma, n = x*r;  dgamma += sum_t da*n (two-stage, deterministic).
 // partial: workspace of rmsnorm_bwd_blocks(T) * h floats.  dres may be null (no residual branch: dx without it).
-// overwrite: dgamma = instead of +=.
+// overwrite: dgamma = instead of +=.  A sequence of calls over several micro-batches may share one column
+// reduction: acc_partial adds this call's row-block sums to those already in `partial` (same T), and only the
+// call with `reduce` adds the columns of `partial` into dgamma (dgamma and overwrite are ignored otherwise).
 int rmsnorm_bwd_blocks(int T);
 hipError_t rmsnorm_bwd(int dt, const void* da, int64_t ld_da, const void* x, int64_t ldx, const void* gamma,
                        const float* r, const void* dres, int64_t ld_dres, void* dx, int64_t ld_dx, float* dgamma,
-                       float* partial, int T, int h, hipStream_t st, bool overwrite = false);
+                       float* partial, int T, int h, hipStream_t st, bool overwrite = false, bool acc_partial = false,
+                       bool reduce = true);
 // rotate the pairs (i, i+d/2) of the first n_heads heads of every row of u [T, ld] by sign*angle(t % S, i)
 hipError_t rope_inplace(int dt, void* u, const float* cos_tab, const float* sin_tab, int T, int S, int n_heads, int d,
                         int64_t ld, float sign, hipStream_t st);

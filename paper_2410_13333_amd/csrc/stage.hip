@@ -108,7 +108,8 @@ struct mls_stage {
   char *g0 = nullptr, *g1 = nullptr, *dz = nullptr, *dgu = nullptr, *dbuf = nullptr, *dh = nullptr, *dc = nullptr,
        *dqkv = nullptr;
   size_t mb_h = 0, mb_gu = 0, mb_qkv = 0;  // bytes per micro-batch of the [T,ld_h], [T,ld_gu], [T,ld_qkv] buffers
-  float *delta = nullptr, *partial = nullptr, *gqa_part = nullptr;  // gqa_part: partial dK/dV sums (few KV heads)
+  // partial, partial2: row-block sums of the two gain gradients of a layer, summed over a call's micro-batches
+  float *delta = nullptr, *partial = nullptr, *partial2 = nullptr, *gqa_part = nullptr;  // gqa_part: partial dK/dV sums (few KV heads)
   std::vector<int> last_k;  // layer counts of the entries of the most recent backward call (for mls_stage_debug_read)
   Timing tm;
 
@@ -225,7 +226,7 @@ int layer_forward(mls_stage* s, int layer, const char* x, char* e, void* out, in
 // dy: gradient w.r.t. the layer output (row stride ld_dy); dx receives the gradient w.r.t. its input (row stride
 // ld_dx); g: this layer's slice of the caller's fp32 gradient vector (gains only here).
 int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, int w, const void* dy, int64_t ld_dy,
-                        void* dx, int64_t ld_dx, float* g, bool ow) {
+                        void* dx, int64_t ld_dx, float* g, bool ow, bool first, bool last) {
   const mls_config& c = s->c;
   const LayerStash& L = s->ls;
   const int T = s->T, h = c.hidden, f = c.ffn, qd = s->qd, wq = s->qkvw;
@@ -238,7 +239,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
   LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st, s->fuse_gu));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
-                                    dy, ld_dy, dh, lh, g + s->off_g2, s->partial, T, h, s->st, ow));
+                                    dy, ld_dy, dh, lh, g + s->off_g2, s->partial2, T, h, s->st, ow, !first, last));
   // attention
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
   LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
@@ -247,7 +248,7 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
                                      c.head_dim, lq, -1.f, s->st));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
-                                    dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st, ow));
+                                    dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st, ow, !first, last));
   return MLS_OK;
 }
 
@@ -343,13 +344,14 @@ std::vector<Alloc> allocations(mls_stage* s) {
       {(void**)&s->dqkv, nmb * s->mb_qkv, 2},
       {(void**)&s->delta, size_t(c.micro_batch) * c.n_q_heads * c.seq * 4, 2},
       {(void**)&s->partial, size_t(nb) * h * 4, 2},
+      {(void**)&s->partial2, size_t(nb) * h * 4, 2},
       {(void**)&s->gqa_part, mls::attn_bwd_scratch_floats(s->dt, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) * 4, 2},
   };
 }
 
 void release(mls_stage* s) {
   void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->rc_scratch, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
-               s->delta, s->partial, s->gqa_part};
+               s->delta, s->partial, s->partial2, s->gqa_part};
   for (void* q : p)
     if (q) (void)hipFree(q);
   for (hipEvent_t e : s->tm.ev) (void)hipEventDestroy(e);
@@ -474,8 +476,11 @@ int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n,
   for (int l = kmax - 1; l >= 0; l--) {
     float* g = grads + size_t(l) * s->layer_params;
     az.clear(); ab.clear(); ao.clear(); aa.clear(); bdy.clear(); bdgu.clear(); bdh.clear(); bdqkv.clear();
+    int have = 0, seen = 0;  // micro-batches of this call that contain layer l
+    for (int i = 0; i < n; i++) have += k[i] > l;
     for (int i = 0; i < n; i++) {
       if (k[i] <= l) continue;
+      seen++;
       const char* x = s->slot_layer(slot[i], l) + L.x;
       const char* e = s->slot_layer(slot[i], l);
       if (c.recompute) {  // rebuild this layer's tensors from its kept input, into scratch entry i
@@ -485,7 +490,7 @@ int mls_stage_backward_ex(mls_stage* s, const void* dY, float* grads, int32_t n,
       }
       const char* dy = pp(i, (l + 1) & 1);
       void* dx = l == 0 ? (void*)((char*)dX + size_t(i) * act) : (void*)pp(i, l & 1);
-      if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g, ow && az.empty())) return rc;
+      if (int rc = layer_backward_data(s, l, x, e, i, dy, s->ld_h, dx, l == 0 ? h : s->ld_h, g, ow, seen == 1, seen == have)) return rc;
       az.push_back(e + L.z); ab.push_back(e + L.b); ao.push_back(e + L.o); aa.push_back(e + L.a);
       bdy.push_back(dy);
       bdgu.push_back(s->dgu + size_t(i) * s->mb_gu);
