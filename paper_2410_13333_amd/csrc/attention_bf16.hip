@@ -132,6 +132,29 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
+// N LDS fragment reads feeding N MFMAs, each read issued DEPTH fragments ahead of its use so that the LDS latency
+// hides behind the MFMAs in between (left to itself the compiler reads every fragment right before its MFMA and
+// waits for it).  read(i) returns fragment i (RPF LDS instructions each), use(i, f) issues the MFMA that takes it.
+template <int N, int DEPTH, int RPF, class Read, class Use>
+__device__ __forceinline__ void read_ahead(Read&& read, Use&& use) {
+  bf16x8 f[N];  // fully unrolled: a fragment's registers are free again once its MFMA has issued
+#pragma unroll
+  for (int i = 0; i < DEPTH && i < N; i++) f[i] = read(i);
+#pragma unroll
+  for (int i = 0; i < N; i++) {
+    if (i + DEPTH < N) f[i + DEPTH] = read(i + DEPTH);
+    use(i, f[i]);
+  }
+  // the issue order the scheduler is asked for: DEPTH fragments, then MFMA / next fragment alternating
+#pragma unroll
+  for (int i = 0; i < DEPTH && i < N; i++) __builtin_amdgcn_sched_group_barrier(0x100, RPF, 0);
+#pragma unroll
+  for (int i = 0; i < N; i++) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (i + DEPTH < N) __builtin_amdgcn_sched_group_barrier(0x100, RPF, 0);
+  }
+}
+
 // store a transposed 32x32 result (col l%32 = token, rows = feature index) as bf16: 4 consecutive features = 8 bytes
 __device__ __forceinline__ void store_t(bf16_t* __restrict__ out, int64_t ld, int token, int col0, const f32x16& a,
                                         float mul, int lane, bool valid) {
@@ -305,37 +328,35 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
     if (j0 <= qw + 31) {
       const bf16_t* ks = lds[cur][0];
       const bf16_t* vs = lds[cur][1];
-      f32x16 st[2], dp[2];
+      const bool diag = j0 + TR - 1 > qw;  // some pair of this wave is masked
+      // one 32-key sub-block at a time, so that only one S^T / dP^T pair is live
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
-        st[jt] = zero16();
-        dp[jt] = zero16();
+        f32x16 st = zero16(), dp = zero16();
+        read_ahead<2 * KD, 3, 1>(
+            [&](int i) { return TL::frag_rows((i & 1) ? vs : ks, jt, i >> 1, lane); },
+            [&](int i, const bf16x8& f) {
+              if (i & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[i >> 1], dp, 0, 0, 0);
+              else st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[i >> 1], st, 0, 0, 0);
+            });
+        // key j = j0 + 32 jt + 4 (lane / 32) + off(e) is masked when j > qi, i.e. off(e) > lim; the mask arithmetic
+        // is compiled only into the diagonal-block path
+        const int lim = qi - (j0 + jt * 32 + (lane >> 5) * 4);
+        auto to_ds = [&](auto MASK) {
 #pragma unroll
-        for (int kk = 0; kk < KD; kk++) {
-          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ks, jt, kk, lane), qf[kk], st[jt], 0, 0, 0);
-          dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(vs, jt, kk, lane), dof[kk], dp[jt], 0, 0, 0);
-        }
+          for (int e = 0; e < 16; e++) {
+            float p = __builtin_amdgcn_exp2f(st[e] * sc - L2);
+            if (decltype(MASK)::value && 8 * (e >> 2) + (e & 3) > lim) p = 0.f;
+            st[e] = p * (dp[e] - dl);
+          }
+        };
+        if (diag) to_ds(std::true_type{}); else to_ds(std::false_type{});
+        const bf16x8 df[2] = {acc_to_b(st, 0), acc_to_b(st, 1)};
+        read_ahead<2 * DT, 2, 2>([&](int i) { return TL::frag_cols(ks, i % DT, jt * 2 + i / DT, lane); },
+                                 [&](int i, const bf16x8& f) {
+                                   acc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, df[i / DT], acc[i % DT], 0, 0, 0);
+                                 });
       }
-      // (one code path with a uniform flag: two specialised paths push this kernel over 256 registers into spills)
-      const bool diag = j0 + TR - 1 > qw;
-#pragma unroll
-      for (int jt = 0; jt < 2; jt++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-          float p = __builtin_amdgcn_exp2f(st[jt][e] * sc - L2);
-          if (diag && j > qi) p = 0.f;
-          st[jt][e] = p * (dp[jt][e] - dl);
-        }
-#pragma unroll
-      for (int jt = 0; jt < 2; jt++)
-#pragma unroll
-        for (int s = 0; s < 2; s++) {
-          const bf16x8 df = acc_to_b(st[jt], s);
-#pragma unroll
-          for (int t = 0; t < DT; t++)
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(ks, t, jt * 2 + s, lane), df, acc[t], 0, 0, 0);
-        }
     }
   }
   wait_dma();
@@ -421,54 +442,51 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
     if (i0 + TR - 1 >= jw) {  // wave-uniform: some query row at or below this wave's first key row
       const bf16_t* qs = lds[cur][0];
       const bf16_t* ds_ = lds[cur][1];
-      f32x16 st[2], dp[DKM ? 2 : 1];
+      const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
+      const bf16_t* tx = DKM ? qs : ds_;
+      // one 32-query sub-block at a time, so that only one S / dP pair is live
 #pragma unroll
       for (int itl = 0; itl < 2; itl++) {
-        st[itl] = zero16();
-        if (DKM) dp[itl] = zero16();
-#pragma unroll
-        for (int kk = 0; kk < KD; kk++) {
-          st[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(qs, itl, kk, lane), kf[kk], st[itl], 0, 0, 0);
-          if (DKM)
-            dp[itl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ds_, itl, kk, lane), vf[kk], dp[itl], 0, 0, 0);
-        }
-      }
-      const bool diag = i0 < jw + 31 || i0 + TR > S;  // some pair is masked, or the block runs past the last row
-      if (DKM) {
-        // (one code path with a uniform flag: a separate mask-free path pushes this kernel over 256 registers)
-#pragma unroll
-        for (int itl = 0; itl < 2; itl++)
-#pragma unroll
-          for (int e = 0; e < 16; e++) {
-            const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-            float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
-            if (diag && (i0 + r < ji || i0 + r >= S)) p = 0.f;
-            st[itl][e] = p * (dp[itl][e] - stat[cur][1][r]);  // dS
-          }
-      } else {
-        auto softmax = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
-#pragma unroll
-          for (int itl = 0; itl < 2; itl++)
+        f32x16 st = zero16(), dp = zero16();
+        if (DKM) {
+          read_ahead<2 * KD, 3, 1>(
+              [&](int i) { return TL::frag_rows((i & 1) ? ds_ : qs, itl, i >> 1, lane); },
+              [&](int i, const bf16x8& f) {
+                if (i & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, vf[DKM ? i >> 1 : 0], dp, 0, 0, 0);
+                else st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, kf[i >> 1], st, 0, 0, 0);
+              });
+          auto to_ds = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
 #pragma unroll
             for (int e = 0; e < 16; e++) {
               const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-              float p = __builtin_amdgcn_exp2f(st[itl][e] * sc - stat[cur][0][r]);
+              float p = __builtin_amdgcn_exp2f(st[e] * sc - stat[cur][0][r]);
               if (decltype(MASK)::value && (i0 + r < ji || i0 + r >= S)) p = 0.f;
-              st[itl][e] = p;
+              st[e] = p * (dp[e] - stat[cur][1][r]);  // dS
             }
-        };
-        if (diag) softmax(std::true_type{}); else softmax(std::false_type{});
-      }
-      const bf16_t* tx = DKM ? qs : ds_;
+          };
+          if (diag) to_ds(std::true_type{}); else to_ds(std::false_type{});
+        } else {
+          read_ahead<KD, 3, 1>([&](int i) { return TL::frag_rows(qs, itl, i, lane); },
+                               [&](int i, const bf16x8& f) {
+                                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, kf[i], st, 0, 0, 0);
+                               });
+          auto softmax = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
 #pragma unroll
-      for (int itl = 0; itl < 2; itl++)
-#pragma unroll
-        for (int s = 0; s < 2; s++) {
-          const bf16x8 bf = acc_to_b(st[itl], s);
-#pragma unroll
-          for (int t = 0; t < DT; t++)
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(tx, t, itl * 2 + s, lane), bf, acc[t], 0, 0, 0);
+            for (int e = 0; e < 16; e++) {
+              const int r = itl * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+              float p = __builtin_amdgcn_exp2f(st[e] * sc - stat[cur][0][r]);
+              if (decltype(MASK)::value && (i0 + r < ji || i0 + r >= S)) p = 0.f;
+              st[e] = p;
+            }
+          };
+          if (diag) softmax(std::true_type{}); else softmax(std::false_type{});
         }
+        const bf16x8 bf[2] = {acc_to_b(st, 0), acc_to_b(st, 1)};
+        read_ahead<2 * DT, 2, 2>([&](int i) { return TL::frag_cols(tx, i % DT, itl * 2 + i / DT, lane); },
+                                 [&](int i, const bf16x8& f) {
+                                   acc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, bf[i / DT], acc[i % DT], 0, 0, 0);
+                                 });
+      }
     }
     if (it + 1 < niter) put_stat(it + 1);
   }
