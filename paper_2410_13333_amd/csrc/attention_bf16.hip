@@ -413,11 +413,13 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
   TL tq, td;
   tq.init(ld, wave, lane);
   td.init(ldo, wave, lane);
+  // The query blocks of a head are walked from the last one down to the diagonal: the workgroups of all key blocks
+  // of that head (same XCD, started together) then read the same Q / dO tile at about the same time and share it in L2.
   // iteration `it`: Q and dO rows of one 64-row query block of one head of the group -> buffer it & 1; the row
   // statistics go through registers (threads 0..63: lse*log2e of row tid; threads 64..127: delta of row tid-64)
   float rs = 0.f;
   auto issue = [&](int it, bool live) {
-    const int hq = hq0 + (live ? it / nqb : 0), i0 = (qb0 + (live ? it % nqb : 0)) * TR;
+    const int hq = hq0 + (live ? it / nqb : 0), i0 = (qb0 + (live ? nqb - 1 - it % nqb : 0)) * TR;
     const uint32_t t = lds0 + (it & 1) * 2 * TL::BYTES;
     tq.dma(rq_src, ld, i0, hq * D, t, wave, live);
     td.dma(rd_src, ldo, i0, hq * D, t + TL::BYTES, wave, live);
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
   issue(0, niter > 0);
   put_stat(0);
   for (int it = 0; it < niter; it++) {
-    const int cur = it & 1, i0 = (qb0 + it % nqb) * TR;
+    const int cur = it & 1, i0 = (qb0 + nqb - 1 - it % nqb) * TR;
     wait_dma();
     __syncthreads();
     issue(it + 1, it + 1 < niter);
