@@ -221,38 +221,42 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
         for (int kk = 0; kk < KD; kk++)
           st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(ks, jt, kk, lane), qf[kk], st[jt], 0, 0, 0);
       }
+      // row maximum of the raw scores (the scale is positive: it commutes with the maximum and is folded into the
+      // exponent below); the mask arithmetic is compiled only into the diagonal-block path
       float mx = -INFINITY;
-      auto scale_mask = [&](auto MASK) {  // the mask arithmetic is compiled only into the diagonal-block path
+      auto mask_max = [&](auto MASK) {
 #pragma unroll
         for (int jt = 0; jt < 2; jt++)
 #pragma unroll
           for (int e = 0; e < 16; e++) {
             const int j = j0 + jt * 32 + (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-            float t = st[jt][e] * sc;
-            if (decltype(MASK)::value && j > qi) t = -INFINITY;
-            st[jt][e] = t;
-            mx = fmaxf(mx, t);
+            if (decltype(MASK)::value && j > qi) st[jt][e] = -INFINITY;
+            mx = fmaxf(mx, st[jt][e]);
           }
       };
-      if (j0 + TR - 1 > qw) scale_mask(std::true_type{}); else scale_mask(std::false_type{});  // some pair masked?
+      if (j0 + TR - 1 > qw) mask_max(std::true_type{}); else mask_max(std::false_type{});  // some pair masked?
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(m, mx);  // finite: block 0 always holds j = 0 <= i
-      const float corr = __builtin_amdgcn_exp2f(m - mn);
+      const float mn = fmaxf(m, mx * sc);  // finite: block 0 always holds j = 0 <= i
       float ps = 0.f;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          const float p = __builtin_amdgcn_exp2f(st[jt][e] - mn);
+          const float p = __builtin_amdgcn_exp2f(st[jt][e] * sc - mn);
           st[jt][e] = p;
           ps += p;
         }
-      l = l * corr + ps;
-      m = mn;
+      // the running maximum rarely moves after the first blocks: rescale only when some row's did
+      if (__any(mn > m)) {
+        const float corr = __builtin_amdgcn_exp2f(m - mn);
+        l *= corr;
 #pragma unroll
-      for (int t = 0; t < DT; t++)
+        for (int t = 0; t < DT; t++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) acc[t][e] *= corr;
+          for (int e = 0; e < 16; e++) acc[t][e] *= corr;
+        m = mn;
+      }
+      l += ps;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
