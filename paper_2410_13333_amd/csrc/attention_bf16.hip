@@ -168,6 +168,39 @@ __device__ __forceinline__ void store_t(bf16_t* __restrict__ out, int64_t ld, in
   }
 }
 
+// The same store for a whole head vector of a gradient w.r.t. rotated q or k, turned back by the rotary angle of
+// its position on the way out (the transpose of the forward rotation): with (g1, g2) the halves of the gradient,
+// the result is (g1 c + g2 s, g2 c - g1 s).  Feature i of the first half sits in tile i / 32, its partner
+// i + D/2 in tile i / 32 + D/64, same register.  cos_tab, sin_tab: [S][D/2] fp32; pos: position in the sequence.
+template <int D>
+__device__ __forceinline__ void store_t_unrotate(bf16_t* __restrict__ out, int64_t ld, int token, int pos, int col0,
+                                                 const f32x16 (&a)[D / 32], float mul, const float* __restrict__ cos_tab,
+                                                 const float* __restrict__ sin_tab, int lane, bool valid) {
+  if (!valid) return;
+  constexpr int H = D / 64, D2 = D / 2;
+#pragma unroll
+  for (int t = 0; t < H; t++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const int f = t * 32 + (lane >> 5) * 4 + 8 * g;
+      const float4 c = *reinterpret_cast<const float4*>(cos_tab + int64_t(pos) * D2 + f);
+      const float4 sn = *reinterpret_cast<const float4*>(sin_tab + int64_t(pos) * D2 + f);
+      const float cs[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+      float o1[4], o2[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const float g1 = a[t][g * 4 + r] * mul, g2 = a[t + H][g * 4 + r] * mul;
+        o1[r] = g1 * cs[r] + g2 * ss[r];
+        o2[r] = g2 * cs[r] - g1 * ss[r];
+      }
+      uint2 v1, v2;
+      v1.x = pack_bf16x2(o1[0], o1[1]); v1.y = pack_bf16x2(o1[2], o1[3]);
+      v2.x = pack_bf16x2(o2[0], o2[1]); v2.y = pack_bf16x2(o2[2], o2[3]);
+      *reinterpret_cast<uint2*>(out + int64_t(token) * ld + col0 + f) = v1;
+      *reinterpret_cast<uint2*>(out + int64_t(token) * ld + col0 + D2 + f) = v2;
+    }
+}
+
 // ================================================================ forward
 // grid (n_q, q blocks of 128, b) with the longest query blocks dispatched first over all heads; wave w owns
 // query rows q0 + 32w .. +31; loops over KV blocks of 64.  Two workgroups fit a CU.
@@ -286,7 +319,8 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta,
                                                                 bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
-                                                                int nkv) {
+                                                                int nkv, const float* __restrict__ cos_tab,
+                                                                const float* __restrict__ sin_tab) {
   using TL = Tile<D>;
   constexpr int KD = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][TR * D];
@@ -365,8 +399,12 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
   }
   wait_dma();
   bf16_t* out = dqkv + int64_t(bi) * S * ldg;
+  if (cos_tab) {  // the gradient w.r.t. the rotated q, turned back to the projection's output on the way out
+    store_t_unrotate<D>(out, ldg, qi, qi, hq * D, acc, scale, cos_tab, sin_tab, lane, qi < S);
+  } else {
 #pragma unroll
-  for (int t = 0; t < DT; t++) store_t(out, ldg, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
+    for (int t = 0; t < DT; t++) store_t(out, ldg, qi, hq * D + t * 32, acc[t], scale, lane, qi < S);
+  }
 }
 
 // ================================================================ backward: dK and dV (one kernel each)
@@ -384,7 +422,9 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
                                                                  const float* __restrict__ lse,
                                                                  const float* __restrict__ delta,
                                                                  bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
-                                                                 int nkv, int nsplit, float* __restrict__ part) {
+                                                                 int nkv, int nsplit, float* __restrict__ part,
+                                                                 const float* __restrict__ cos_tab,
+                                                                 const float* __restrict__ sin_tab) {
   using TL = Tile<D>;
   constexpr bool DKM = WHAT == 0;
   constexpr int KD = D / 16, DT = D / 32;
@@ -499,9 +539,13 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
   wait_dma();
   if (nsplit == 1) {
     bf16_t* out = dqkv + int64_t(bi) * S * ldg;
+    if (DKM && cos_tab) {  // dK is a gradient w.r.t. the rotated k (partial sums are turned back by the reduction)
+      store_t_unrotate<D>(out, ldg, ji, ji, (nq + hk) * D, acc, scale, cos_tab, sin_tab, lane, ji < S);
+    } else {
 #pragma unroll
-    for (int t = 0; t < DT; t++)
-      store_t(out, ldg, ji, (DKM ? nq + hk : nq + nkv + hk) * D + t * 32, acc[t], DKM ? scale : 1.f, lane, ji < S);
+      for (int t = 0; t < DT; t++)
+        store_t(out, ldg, ji, (DKM ? nq + hk : nq + nkv + hk) * D + t * 32, acc[t], DKM ? scale : 1.f, lane, ji < S);
+    }
   } else if (ji < S) {
     // part: [dK | dV][b][n_kv][nsplit][S][D] fp32
     float* out = part + ((((int64_t(WHAT) * gridDim.z + bi) * nkv + hk) * nsplit + sp) * S + ji) * D;
@@ -515,11 +559,15 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dkv_kernel(const bf16_t* _
   }
 }
 
-// dK, dV <- the partial sums of the nsplit workgroups of each KV head, added in ascending order (8 features per thread)
+// dK, dV <- the partial sums of the nsplit workgroups of each KV head, added in ascending order.  A thread owns 8
+// features of the first half of a head vector and their 8 partners in the second half, so that dK (a gradient
+// w.r.t. the rotated k) can be turned back by the rotary angle when the tables are given.
 __global__ __launch_bounds__(256) void gqa_reduce_kernel(const float* __restrict__ part, int nsplit, int b, int S, int D,
-                                                         int nq, int nkv, bf16_t* __restrict__ dqkv, int64_t ldg) {
+                                                         int nq, int nkv, bf16_t* __restrict__ dqkv, int64_t ldg,
+                                                         const float* __restrict__ cos_tab,
+                                                         const float* __restrict__ sin_tab) {
   const int64_t id = int64_t(blockIdx.x) * 256 + threadIdx.x;
-  const int cpr = D >> 3;
+  const int d2 = D >> 1, cpr = d2 >> 3;
   const int64_t total = int64_t(2) * b * nkv * S * cpr;
   if (id >= total) return;
   const int c = int(id % cpr) * 8;
@@ -527,14 +575,31 @@ __global__ __launch_bounds__(256) void gqa_reduce_kernel(const float* __restrict
   const int token = int(row % S);
   const int hk = int((row / S) % nkv), bi = int((row / S / nkv) % b), what = int(row / S / nkv / b);
   const float* p = part + ((((int64_t(what) * b + bi) * nkv + hk) * nsplit) * S + token) * D + c;
-  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float a1[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, a2[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int sp = 0; sp < nsplit; sp++) {
-    float v[8];
-    load8(p + int64_t(sp) * S * D, v);
+    float v1[8], v2[8];
+    load8(p + int64_t(sp) * S * D, v1);
+    load8(p + int64_t(sp) * S * D + d2, v2);
 #pragma unroll
-    for (int e = 0; e < 8; e++) a[e] += v[e];
+    for (int e = 0; e < 8; e++) {
+      a1[e] += v1[e];
+      a2[e] += v2[e];
+    }
   }
-  store8(dqkv + (int64_t(bi) * S + token) * ldg + (what ? nq + nkv + hk : nq + hk) * D + c, a);
+  if (what == 0 && cos_tab) {
+    float cs[8], sn[8];
+    load8(cos_tab + int64_t(token) * d2 + c, cs);
+    load8(sin_tab + int64_t(token) * d2 + c, sn);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float g1 = a1[e], g2 = a2[e];
+      a1[e] = g1 * cs[e] + g2 * sn[e];
+      a2[e] = g2 * cs[e] - g1 * sn[e];
+    }
+  }
+  bf16_t* out = dqkv + (int64_t(bi) * S + token) * ldg + (what ? nq + nkv + hk : nq + hk) * D + c;
+  store8(out, a1);
+  store8(out + d2, a2);
 }
 
 }  // namespace
@@ -576,33 +641,34 @@ size_t attn_bwd_scratch_floats(int dt, int b, int S, int nq, int nkv, int d) {
 
 hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
                          int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
-                         hipStream_t st, float* part) {
+                         hipStream_t st, float* part, const float* cos_tab, const float* sin_tab) {
   if (b == 0 || S == 0) return hipSuccess;
+  if (!cos_tab != !sin_tab) return hipErrorInvalidValue;
   hipError_t e = attn_delta(DT_BF16, o, ld_o, d_o, ld_do, delta, b, S, nq, d, st);
   if (e != hipSuccess) return e;
   const int ns = part ? gqa_split(b, S, nq, nkv) : 1;
   dim3 gq(nq, (S + 127) / 128, b), gk(nkv * ns, (S + 127) / 128, b);
   if (d == 128) {
     hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
   } else if (d == 64) {
     hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv);
+                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
-                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part);
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
   } else {
     return hipErrorInvalidValue;
   }
   if (ns > 1) {
-    const int64_t total = int64_t(2) * b * nkv * S * (d >> 3);
+    const int64_t total = int64_t(2) * b * nkv * S * (d >> 4);
     hipLaunchKernelGGL(gqa_reduce_kernel, dim3(unsigned((total + 255) / 256)), dim3(256), 0, st, part, ns, b, S, d, nq, nkv,
-                       (bf16_t*)dqkv, ld_dqkv);
+                       (bf16_t*)dqkv, ld_dqkv, cos_tab, sin_tab);
   }
   return hipGetLastError();
 }
@@ -614,9 +680,10 @@ hipError_t attn_fwd(int dt, const void* qkv, int64_t ld_qkv, void* o, int64_t ld
 }
 hipError_t attn_bwd(int dt, const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse,
                     const void* d_o, int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq,
-                    int nkv, int d, hipStream_t st, float* part) {
+                    int nkv, int d, hipStream_t st, float* part, const float* cos_tab, const float* sin_tab) {
+  if (dt != DT_BF16 && cos_tab) return hipErrorInvalidValue;  // only the bf16 kernels turn the rotation back themselves
   return dt == DT_BF16
-             ? attn_bwd_bf16(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st, part)
+             ? attn_bwd_bf16(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st, part, cos_tab, sin_tab)
              : attn_bwd_f32(qkv, ld_qkv, o, ld_o, lse, d_o, ld_do, dqkv, ld_dqkv, delta, b, S, nq, nkv, d, st);
 }
 

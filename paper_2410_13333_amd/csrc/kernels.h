@@ -91,11 +91,14 @@ hipError_t attn_fwd(int dt, const void* qkv, int64_t ld_qkv, void* o, int64_t ld
 // dqkv has the column layout of qkv; delta: workspace [b, n_q, S] fp32 (row sums of do*o); part: workspace of
 // attn_bwd_scratch_floats() floats, or null.  With few KV heads the dK / dV kernels share the query heads of a
 // group out over several workgroups, which leave fp32 partial sums in `part` for a fixed-order reduction; without
-// the workspace one workgroup walks the whole group.
+// the workspace one workgroup walks the whole group.  cos_tab, sin_tab ([S][d/2] fp32, bf16 storage only): the q and
+// k parts of dqkv come out turned back by the rotary angle of their position, i.e. as gradients w.r.t. the
+// projection's output; without them they are gradients w.r.t. the rotated q and k.
 size_t attn_bwd_scratch_floats(int dt, int b, int S, int nq, int nkv, int d);
 hipError_t attn_bwd(int dt, const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse,
                     const void* d_o, int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq,
-                    int nkv, int d, hipStream_t st, float* part = nullptr);
+                    int nkv, int d, hipStream_t st, float* part = nullptr, const float* cos_tab = nullptr,
+                    const float* sin_tab = nullptr);
 
 // pieces behind the two dispatchers above
 hipError_t attn_delta(int dt, const void* o, int64_t ld_o, const void* d_o, int64_t ld_do, float* delta, int b, int S,
@@ -109,6 +112,6 @@ hipError_t attn_fwd_bf16(const void* qkv, int64_t ld_qkv, void* o, int64_t ld_o,
                          int d, hipStream_t st);
 hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t ld_o, const float* lse, const void* d_o,
                          int64_t ld_do, void* dqkv, int64_t ld_dqkv, float* delta, int b, int S, int nq, int nkv, int d,
-                         hipStream_t st, float* part);
+                         hipStream_t st, float* part, const float* cos_tab, const float* sin_tab);
 
 }  // namespace mls

@@ -242,10 +242,14 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
                                     dy, ld_dy, dh, lh, g + s->off_g2, s->partial2, T, h, s->st, ow, !first, last));
   // attention
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
+  // the bf16 attention-backward kernels turn dq and dk back by the rotary angle as they store them
+  const bool unrot = s->dt == mls::DT_BF16;
   LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
-                                     s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st, s->gqa_part));
-  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
-                                     c.head_dim, lq, -1.f, s->st));
+                                     s->delta, c.micro_batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, s->st, s->gqa_part,
+                                     unrot ? s->cos_tab : nullptr, unrot ? s->sin_tab : nullptr));
+  if (!unrot)
+    LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
+                                       c.head_dim, lq, -1.f, s->st));
   LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
                                     dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st, ow, !first, last));
