@@ -1,5 +1,6 @@
 // Causal grouped-query attention for bf16 storage on the gfx950 matrix cores: forward with online softmax,
-// backward as three kernels (dQ; dK; dV) that recompute the probabilities from the saved log-sum-exp.
+// backward as three kernels (dQ, which also forms the row sums delta = dO . O; dK; dV) that recompute the
+// probabilities from the saved log-sum-exp.
 // Nothing of size S x S is ever written; no float atomics, so results are bitwise reproducible.
 //
 // Register-resident probabilities.  v_mfma_f32_32x32x16_bf16 leaves element (g*4+r) of lane l at
@@ -315,9 +316,10 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
 // dQ^T += K^T dS^T.
 template <int D>
 __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv, int64_t ld,
+                                                                const bf16_t* __restrict__ o, int64_t ld_o,
                                                                 const bf16_t* __restrict__ d_o, int64_t ldo,
                                                                 const float* __restrict__ lse,
-                                                                const float* __restrict__ delta,
+                                                                float* __restrict__ delta,
                                                                 bf16_t* __restrict__ dqkv, int64_t ldg, int S, int nq,
                                                                 int nkv, const float* __restrict__ cos_tab,
                                                                 const float* __restrict__ sin_tab) {
@@ -349,7 +351,20 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_dq_kernel(const bf16_t* __
   }
   const int64_t si = (int64_t(bi) * nq + hq) * S + qi;
   const float L2 = qi < S ? lse[si] * LOG2E : 0.f;
-  const float dl = qi < S ? delta[si] : 0.f;
+  // delta = dO . O of this lane's query row (the two lane halves hold complementary features); it is also
+  // written out for the dK kernel, which runs after this one
+  float dl = 0.f;
+  {
+    const bf16_t* ob = o + int64_t(bi) * S * ld_o;
+#pragma unroll
+    for (int kk = 0; kk < KD; kk++) {
+      const bf16x8 of = gfrag(ob, ld_o, qi, hq * D + kk * 16 + (lane >> 5) * 8, qi < S);
+#pragma unroll
+      for (int e = 0; e < 8; e++) dl += (float)of[e] * (float)dof[kk][e];
+    }
+    dl += __shfl_xor(dl, 32, 64);
+    if (lane < 32 && qi < S) delta[si] = dl;
+  }
 
   f32x16 acc[DT];
 #pragma unroll
@@ -644,20 +659,18 @@ hipError_t attn_bwd_bf16(const void* qkv, int64_t ld_qkv, const void* o, int64_t
                          hipStream_t st, float* part, const float* cos_tab, const float* sin_tab) {
   if (b == 0 || S == 0) return hipSuccess;
   if (!cos_tab != !sin_tab) return hipErrorInvalidValue;
-  hipError_t e = attn_delta(DT_BF16, o, ld_o, d_o, ld_do, delta, b, S, nq, d, st);
-  if (e != hipSuccess) return e;
   const int ns = part ? gqa_split(b, S, nq, nkv) : 1;
   dim3 gq(nq, (S + 127) / 128, b), gk(nkv * ns, (S + 127) / 128, b);
   if (d == 128) {
-    hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
+    hipLaunchKernelGGL(attn_dq_kernel<128>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)o, ld_o,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
                        (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<128, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
                        (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
   } else if (d == 64) {
-    hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)d_o,
-                       ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
+    hipLaunchKernelGGL(attn_dq_kernel<64>, gq, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv, (const bf16_t*)o, ld_o,
+                       (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 0>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
                        (const bf16_t*)d_o, ld_do, lse, delta, (bf16_t*)dqkv, ld_dqkv, S, nq, nkv, ns, part, cos_tab, sin_tab);
     hipLaunchKernelGGL((attn_dkv_kernel<64, 1>), gk, dim3(AT_THREADS), 0, st, (const bf16_t*)qkv, ld_qkv,
