@@ -24,12 +24,14 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+// EPI_ROPE: C = acc rounded to bf16, then the head vectors in columns below rot_cols rotated by the rotary angle of
+// their row's position (row % seq), pairs (i, i + head_dim/2); the remaining columns (v) are stored as they are.
 // Epilogues.  EPI_BF16: C = acc (+ R), bf16.  EPI_F32_ACC: C += acc, fp32 (C = acc when `ldx` != 0); with `xf` > 0
 // the columns are the gate/up-interleaved order and are written to their public places (see gu_public_col).  EPI_SWIGLU: N = 2f
 // interleaved columns [gate | up]; C receives both (bf16) and X[row][f] their SwiGLU product.  (The SwiGLU backward
 // as an epilogue of the dZ contraction was measured slower than a separate kernel: the epilogue's extra reads are
 // fully exposed with one workgroup per CU.)
-enum { EPI_BF16 = 0, EPI_F32_ACC = 1, EPI_SWIGLU = 2 };
+enum { EPI_BF16 = 0, EPI_F32_ACC = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
 enum { PIPE_PLAIN = 0, PIPE_SKEW = 1 };
 
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_byte) {
@@ -65,6 +67,12 @@ struct SegArgs {
   const bf16_t* a[MAX_SEGS];
   const bf16_t* b[MAX_SEGS];
   int nseg, kseg;
+};
+// rotary tables [seq][head_dim/2] fp32 and the column range they apply to (EPI_ROPE)
+struct RopeArgs {
+  const float* cos_tab;
+  const float* sin_tab;
+  int seq, rot_cols, head_dim;
 };
 
 // ---- [row][k] tile: ROWS x BK elements, BK*2 bytes per row
@@ -137,7 +145,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
                                                        int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
                                                        int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, int tiles_m,
                                                        int col0, void* __restrict__ Xv, int64_t ldx, int xf,
-                                                       SegArgs segs) {
+                                                       SegArgs segs, RopeArgs rope) {
   using AT_R = RowTile<BM, BK, NW>;
   using AT_C = ColTile<BM, BK, NW>;
   using BT_R = RowTile<BN, BK, NW>;
@@ -384,6 +392,44 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
           *reinterpret_cast<uint2*>(wz + r32 * ZRB + ((zc ^ ((r32 / ZRPL) & (ZNCH - 1))) << 4) + hi * 8) = zo;
         }
       }
+      if (EPI == EPI_ROPE) {
+        // A head of 128 columns spans this wave's 64 and those of the wave next to it along N (wave ^ 2): the
+        // partner's staged rows are read once every wave has staged its own.  A head of 64 columns is the wave's own.
+        const bool wide = rope.head_dim == 128;
+        if (wide) __syncthreads(); else wave_lds_sync();
+        const bool rot = col0 + n0 + wn < rope.rot_cols;  // whole heads: uniform over the wave
+        const unsigned char* pw = wide ? smem + (wave ^ 2) * (64 * 1024 / NW) : ws;
+        const int pch = wide ? cch : cch ^ 4;                        // the partner's chunk of the same row
+        const bool first = wide ? !((wave >> 1) & 1) : cch < 4;      // this lane holds the first halves of its pairs
+        const int d2 = rope.head_dim >> 1, i0 = (wide ? cch : cch & 3) * 8;
+#pragma unroll
+        for (int t = 0; t < NT; t++) {
+          const int lrow = t * RPI + crow, row = row0 + lrow;
+          uint4 o = *reinterpret_cast<const uint4*>(stage_at(lrow, cch));
+          if (rot && row < M && col_ok) {
+            const uint4 q = *reinterpret_cast<const uint4*>(pw + lrow * RB + ((pch ^ ((lrow / RPL) & (NCH - 1))) << 4));
+            const int64_t at = int64_t(row % rope.seq) * d2 + i0;
+            float cs[8], sn[8];
+            load8(rope.cos_tab + at, cs);
+            load8(rope.sin_tab + at, sn);
+            const uint32_t ow[4] = {o.x, o.y, o.z, o.w}, qw[4] = {q.x, q.y, q.z, q.w};
+            uint32_t r[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const float a0 = __uint_as_float(ow[e] << 16), a1 = __uint_as_float(ow[e] & 0xffff0000u);
+              const float b0 = __uint_as_float(qw[e] << 16), b1 = __uint_as_float(qw[e] & 0xffff0000u);
+              // first half: u1 c - u2 s with u1 own, u2 partner; second half: u1 s + u2 c with u1 partner, u2 own
+              const float v0 = first ? a0 * cs[2 * e] - b0 * sn[2 * e] : b0 * sn[2 * e] + a0 * cs[2 * e];
+              const float v1 = first ? a1 * cs[2 * e + 1] - b1 * sn[2 * e + 1] : b1 * sn[2 * e + 1] + a1 * cs[2 * e + 1];
+              r[e] = pack_bf16x2(v0, v1);
+            }
+            o = make_uint4(r[0], r[1], r[2], r[3]);
+          }
+          if (row < M && col_ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(Cv) + int64_t(row) * ldc + ccol) = o;
+        }
+        if (wide) __syncthreads(); else wave_lds_sync();
+        continue;
+      }
       wave_lds_sync();
 #pragma unroll
       for (int t = 0; t < NT; t++) {
@@ -411,16 +457,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
 template <int BM, int BN, int BK, int NS, bool ATR, bool BTR, int EPI, int PIPE = PIPE_PLAIN, bool SEG = false, int NW = 4>
 hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                   int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
-                  const SegArgs* segs = nullptr, int col0 = 0, void* X = nullptr, int64_t ldx = 0, int xf = 0) {
+                  const SegArgs* segs = nullptr, int col0 = 0, void* X = nullptr, int64_t ldx = 0, int xf = 0,
+                  const RopeArgs* rope = nullptr) {
   constexpr int LDS = NS * (BM + BN) * BK * 2;
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;
+  RopeArgs ra = {};
+  if (rope) ra = *rope;
   static std::atomic<uint64_t> lds_raised{0};
   if (hipError_t e = mls::raise_lds_limit(reinterpret_cast<const void*>(kern), LDS, lds_raised)) return e;
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(NW * 64), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, a_bytes, b_bytes, tm,
-                     col0, X, ldx, xf, sa);
+                     col0, X, ldx, xf, sa, ra);
   return hipGetLastError();
 }
 
@@ -442,6 +491,7 @@ struct Extra {
   void* X = nullptr;
   int64_t ldx = 0;
   int xf = 0;
+  const RopeArgs* rope = nullptr;
 };
 
 // A problem may run as two launches over column ranges; they never offset C, R or X: the kernel adds `col0`, the
@@ -464,19 +514,19 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
     const int n1 = split_columns(M, N);
     if (n1 > 0) {
       hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
-                                                                             nullptr, 0, x.X, x.ldx, x.xf);
+                                                                             nullptr, 0, x.X, x.ldx, x.xf, x.rope);
       if (e != hipSuccess) return e;
       // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
       const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
       const uint32_t bb2 = BTR ? bb : uint32_t(int64_t(N - n1) * ldb * 2);
       return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st,
-                                                            nullptr, n1, x.X, x.ldx, x.xf);
+                                                            nullptr, n1, x.X, x.ldx, x.xf, x.rope);
     }
     return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
-                                                                   x.X, x.ldx, x.xf);
+                                                                   x.X, x.ldx, x.xf, x.rope);
   }
   return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0, x.X,
-                                                 x.ldx, x.xf);
+                                                 x.ldx, x.xf, x.rope);
 }
 
 }  // namespace
@@ -557,6 +607,23 @@ hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int
   return dispatch<false, true, EPI_SWIGLU>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), GU, nullptr, M,
                                            2 * f, K, lda, ldw, ldgu, 0, uint32_t(int64_t(M) * lda * 2),
                                            uint32_t(int64_t(K) * ldw * 2), st, x);
+}
+
+bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim) {
+  return (head_dim == 64 || head_dim == 128) && seq > 0 && rot_cols >= 0 && rot_cols <= N && rot_cols % head_dim == 0 &&
+         N % head_dim == 0 && gemm_bf16_dma_ok(GEMM_NN, M, N, K, lda, ldw);
+}
+
+hipError_t gemm_bf16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
+                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st) {
+  if (M == 0 || N == 0) return hipSuccess;
+  if (!cos_tab || !sin_tab || !gemm_rope_ok(M, N, K, lda, ldw, seq, rot_cols, head_dim)) return hipErrorInvalidValue;
+  const RopeArgs ra = {cos_tab, sin_tab, seq, rot_cols, head_dim};
+  Extra x;
+  x.rope = &ra;
+  return dispatch<false, true, EPI_ROPE>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), C, nullptr, M, N, K,
+                                         lda, ldw, ldc, 0, uint32_t(int64_t(M) * lda * 2), uint32_t(int64_t(K) * ldw * 2),
+                                         st, x);
 }
 
 }  // namespace mls

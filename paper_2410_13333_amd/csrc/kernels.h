@@ -51,6 +51,12 @@ hipError_t fill_zero_f32(float* p, size_t n, hipStream_t st);
 bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw);
 hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int f, int K, int64_t lda,
                             int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st);
+// The rotary embedding fused into the q|k|v projection (bf16, DMA path): C[M, N] = A[M,K] W[K,N] rounded to bf16, then
+// every head vector (head_dim = 64 or 128 columns) in the columns below rot_cols rotated by the angle of its row's
+// position row % seq, pairs (i, i + head_dim/2); cos_tab, sin_tab: [seq][head_dim/2] fp32.
+bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim);
+hipError_t gemm_bf16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
+                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st);
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st);
 

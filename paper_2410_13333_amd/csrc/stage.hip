@@ -90,6 +90,7 @@ struct mls_stage {
   // SwiGLU runs as the epilogue of the gate/up contraction; w_gu, gu and dgu are then kept in the interleaved
   // gate/up column order (bf16 storage, ffn % 32 == 0)
   bool fuse_gu = false;
+  bool fuse_rope = false;  // the forward rotary step runs as the epilogue of the q|k|v projection (bf16 storage)
   size_t ilayer_params;  // elements per layer, internal (row-padded) layout
   size_t ioff_g1, ioff_wqkv, ioff_wo, ioff_g2, ioff_wgu, ioff_wd;
   char* params = nullptr;  // storage type, internal layout
@@ -201,9 +202,14 @@ int layer_forward(mls_stage* s, int layer, const char* x, char* e, void* out, in
   const int64_t lh = s->ld_h, lq = s->ld_qkv, lo = s->ld_qd, lg = s->ld_gu, lf = s->ld_f;
   LAUNCH(CLS_NORM, mls::rmsnorm_fwd(s->dt, x, lh, s->param(layer, s->ioff_g1), e + L.a, lh, (float*)(e + L.r1), T, h,
                                     c.rms_eps, s->st));
-  LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->ioff_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, lh, lq, lq));
-  LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
-                                     c.head_dim, lq, 1.f, s->st));
+  if (s->fuse_rope) {  // the rotation of q and k is the epilogue of their projection
+    LAUNCH(CLS_GEMM_NN, mls::gemm_bf16_rope(e + L.a, s->param(layer, s->ioff_wqkv), e + L.qkv, T, s->qkvw, h, lh, lq, lq, s->cos_tab,
+                                            s->sin_tab, c.seq, s->qd + s->kvd, c.head_dim, s->st));
+  } else {
+    LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.a, s->param(layer, s->ioff_wqkv), e + L.qkv, nullptr, T, s->qkvw, h, lh, lq, lq));
+    LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, e + L.qkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
+                                       c.head_dim, lq, 1.f, s->st));
+  }
   LAUNCH(CLS_ATTN_FWD, mls::attn_fwd(s->dt, e + L.qkv, lq, e + L.o, lo, (float*)(e + L.lse), c.micro_batch, c.seq,
                                      c.n_q_heads, c.n_kv_heads, c.head_dim, s->st));
   LAUNCH(CLS_GEMM_NN, gemm(s, mls::GEMM_NN, e + L.o, s->param(layer, s->ioff_wo), e + L.h, x, T, h, s->qd, lo, lh, lh, lh));
@@ -302,6 +308,9 @@ void layout(mls_stage* s) {
   s->ilayer_params = s->ioff_wd + f * s->ld_h;
   s->fuse_gu = s->dt == mls::DT_BF16 && mls::gemm_swiglu_ok(s->T, c.ffn, c.hidden, s->ld_h, s->ld_gu) &&
                mls::gemm_tn_segments_ok(s->T, s->ld_h, s->ld_gu);
+
+  s->fuse_rope = s->dt == mls::DT_BF16 && mls::gemm_rope_ok(s->T, s->qkvw, c.hidden, s->ld_h, s->ld_qkv, c.seq,
+                                                            s->qd + s->kvd, c.head_dim);
 
   LayerStash& L = s->ls;
   size_t o = 0;

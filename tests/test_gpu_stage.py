@@ -276,3 +276,37 @@ def test_token_counts_that_are_not_multiples_of_eight(seq, mb):
                               layers=2, microbatches=2)
         _check(sh, [2, 1], 1e-2)
     _check(sh.with_(dtype="fp32", head_dim=16), [2, 1], 1e-4)
+
+
+@pytest.mark.parametrize("nq,nkv,d,seq,mb", [(30, 2, 128, 4096, 1), (60, 4, 64, 4096, 1), (6, 2, 128, 1000, 3),
+                                              (6, 2, 64, 1000, 3)])
+def test_rotary_epilogue_of_the_qkv_projection(nq, nkv, d, seq, mb):
+    """q|k|v after the rotary step, read back from the stash, against RMSNorm -> projection -> rotation in fp64 with
+    the same bf16 storage points.  The shapes take the projection through every tiling of its kernel: (30, 2, 128)
+    and (60, 4, 64) at 4096 tokens give 17 column tiles of 256 = a full round of 256x256 tiles plus a 256x128 tail
+    launch; 3000 tokens x 1280 / 640 columns run on the 128x128 tiles with ragged rows.  The positions restart
+    with every sequence of the micro-batch."""
+    import paper_2410_13333_amd as mls
+    import oracle.stage as O
+    sh = synth.StageShape(hidden=256, n_q_heads=nq, n_kv_heads=nkv, head_dim=d, ffn=64, seq=seq, micro_batch=mb,
+                          layers=1, microbatches=1)
+    st = mls.Stage.from_shape(sh, seed=1000)
+    xbits, x = synth.make_x(sh, 2000, 0)
+    xd = to_device(xbits, "bf16")
+    import torch
+    y = torch.empty_like(xd)
+    st.forward(xd, 1, y)
+    got = to_host64(st.debug_read("qkv"))
+    st.close()
+    _, p64 = synth.make_params(sh, 1000)
+    w = synth.split_params(sh, p64, 0)
+    a, _ = O.rmsnorm_fwd(x.reshape(seq * mb, sh.hidden), w["gamma1"], sh.rms_eps)
+    pre = bf16_store("qkv_pre", bf16_store("a", a) @ w["w_qkv"])
+    qd, kvd = nq * d, nkv * d
+    rot = O.rope_apply(pre[:, :qd + kvd].reshape(mb, seq, nq + nkv, d), O.rope_angles(seq, d, sh.rope_base))
+    ref = np.concatenate([bf16_store("qkv", rot).reshape(seq * mb, qd + kvd), pre[:, qd + kvd:]], axis=1)
+    for name, lo, hi in (("q", 0, qd), ("k", qd, qd + kvd), ("v", qd + kvd, qd + 2 * kvd)):
+        e = rel_err(got[:, lo:hi], ref[:, lo:hi])
+        assert e <= 3e-3, (name, e)
+    # per-head check on the last head of k and the last rows: a wrong pairing or position would be O(1) there
+    assert rel_err(got[-64:, qd + kvd - d:qd + kvd], ref[-64:, qd + kvd - d:qd + kvd]) <= 3e-3
