@@ -473,17 +473,29 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
   return hipGetLastError();
 }
 
-// When the 256x256 tiles fill the 256 CUs a whole number of times plus a short remainder, the remainder would
-// still cost a full round.  Returns the number of leading columns (a multiple of 256) to run with 256x256 tiles
-// so that they fill whole rounds; the columns after them are run with 256x128 tiles, whose partial round costs
-// about half as much.  0 = do not split.
-int split_columns(int M, int N) {
-  const int tm = (M + 255) / 256, tn = (N + 255) / 256, tiles = tm * tn;
-  const int full = tiles / 256 * 256, rest = tiles - full;
-  if (full == 0 || rest == 0 || rest > 128) return 0;  // remainder above half a round: nothing to gain
-  const int n1_tiles = full / tm;
-  if (n1_tiles <= 0 || n1_tiles >= tn) return 0;
-  return n1_tiles * 256;
+// Tiling plan of one problem.  256x256 tiles (one workgroup per CU) run whole rounds of the 256 CUs; what is left
+// over would still cost a full round, so the trailing columns may run as a second launch of smaller tiles instead:
+// 256x128 (half the work per workgroup) or 128x128 (a quarter, at about three quarters of the big tile's rate).
+// The choice minimises rounds x work per workgroup / relative rate, the rates being measured ones (13B stage: a
+// 128x128 tail of 64 tiles' worth takes 0.29 of a round against 0.5 as 256x128 tiles on half the CUs; 7B stage:
+// three rounds of 128x128 tiles for 176 tiles' worth are no faster than one round of 256x256).
+enum { TAIL_NONE = 0, TAIL_256x128 = 1, TAIL_128x128 = 2 };
+struct ColumnPlan {
+  int n1;    // leading columns (a multiple of 256, possibly 0) run with 256x256 tiles
+  int tail;  // TAIL_*: how the columns from n1 on run (TAIL_NONE: n1 == N, everything is 256x256)
+};
+ColumnPlan plan_columns(int M, int N) {
+  constexpr int CUS = 256;
+  const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+  const int n1_tiles = int(int64_t(tm) * tn / CUS * CUS / tm);  // whole rounds' worth of tile columns
+  const int rest_cols = N - n1_tiles * 256;
+  if (rest_cols <= 0) return {N, TAIL_NONE};
+  auto rounds = [&](int64_t wgs) { return double((wgs + CUS - 1) / CUS); };
+  const double a = rounds(int64_t(tm) * ((rest_cols + 255) / 256));
+  const double b = rounds(int64_t(tm) * ((rest_cols + 127) / 128)) * 0.5 / 0.95;
+  const double c = rounds(int64_t((M + 127) / 128) * ((rest_cols + 127) / 128)) * 0.25 / 0.75;
+  if (a <= b && a <= c) return {N, TAIL_NONE};
+  return {n1_tiles * 256, b <= c ? TAIL_256x128 : TAIL_128x128};
 }
 
 // Extra operands of the fused epilogues (see the EPI_* list)
@@ -500,7 +512,6 @@ template <bool ATR, bool BTR, int EPI>
 hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st,
                     const Extra& x = Extra()) {
-  const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
   // Measured on the 7B stage: with a transposed-read operand (forward, weight gradient) four 32-deep stages in
   // the skewed pipeline win; with two [row][k] operands (data gradient) two 64-deep stages win.  Deeper pipelines
   // and a two-stage loop with its barrier ahead of the last substep all measured within noise of these or slower.
@@ -508,24 +519,21 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
   // Wavefronts per 256x256 workgroup, by measurement on the 7B stage: the bf16-epilogue modes run 8 (two per SIMD,
   // 128x64 each: the second wavefront covers the first one's barrier and load waits; forward -5 %, data gradient
   // -3 %), the fp32 read-modify-write mode runs 4 (128x128 each; 8 measured 2.5 % slower there).
-  constexpr bool nw8 = EPI != EPI_F32_ACC;
-  constexpr int NW = nw8 ? 8 : 4;
-  if (big_tiles >= 192) {
-    const int n1 = split_columns(M, N);
-    if (n1 > 0) {
-      hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, n1, K, lda, ldb, ldc, ldr, ab, bb, st,
-                                                                             nullptr, 0, x.X, x.ldx, x.xf, x.rope);
-      if (e != hipSuccess) return e;
-      // the columns of B: a pointer offset for [k][n], a row offset for [n][k]
-      const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
-      const uint32_t bb2 = BTR ? bb : uint32_t(int64_t(N - n1) * ldb * 2);
-      return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st,
-                                                            nullptr, n1, x.X, x.ldx, x.xf, x.rope);
-    }
-    return launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0,
-                                                                   x.X, x.ldx, x.xf, x.rope);
+  constexpr int NW = EPI != EPI_F32_ACC ? 8 : 4;
+  const ColumnPlan cp = plan_columns(M, N);
+  if (cp.n1 > 0) {
+    hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, cp.n1, K, lda, ldb, ldc, ldr, ab, bb, st,
+                                                                           nullptr, 0, x.X, x.ldx, x.xf, x.rope);
+    if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
   }
-  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, st, nullptr, 0, x.X,
+  // the columns of B from n1 on: a pointer offset for [k][n], a row offset for [n][k]
+  const int n1 = cp.n1;
+  const bf16_t* b2 = BTR ? B + n1 : B + int64_t(n1) * ldb;
+  const uint32_t bb2 = BTR ? bb : uint32_t(int64_t(N - n1) * ldb * 2);
+  if (cp.tail == TAIL_256x128)
+    return launch<256, 128, BK, NS, ATR, BTR, EPI, PIPE>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st, nullptr, n1,
+                                                          x.X, x.ldx, x.xf, x.rope);
+  return launch<128, 128, 64, 3, ATR, BTR, EPI>(A, b2, C, R, M, N - n1, K, lda, ldb, ldc, ldr, ab, bb2, st, nullptr, n1, x.X,
                                                  x.ldx, x.xf, x.rope);
 }
 
@@ -573,24 +581,19 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   sa.nseg = nseg;
   sa.kseg = kseg;
   const uint32_t ab = uint32_t(int64_t(kseg) * lda * 2), bb = uint32_t(int64_t(kseg) * ldb * 2);
-  const int64_t big_tiles = int64_t((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192) {
-    const int n1 = split_columns(M, N);
-    if (n1 > 0) {
-      hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
-          sa.a[0], sa.b[0], C, nullptr, M, n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0, gu_f);
-      if (e != hipSuccess) return e;
-      for (int i = 0; i < nseg; i++) sa.b[i] += n1;
-      return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(
-          sa.a[0], sa.b[0], C, nullptr, M, N - n1, kseg, lda, ldb, ldc, 0, ab, bb, st, &sa, n1, nullptr, overwrite ? 1 : 0, gu_f);
-    }
-    return launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
-                                                                              ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0,
-                                                                              gu_f);
+  const ColumnPlan cp = plan_columns(M, N);
+  const int ovw = overwrite ? 1 : 0;
+  if (cp.n1 > 0) {
+    hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, cp.n1, kseg, lda,
+                                                                                    ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, ovw, gu_f);
+    if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
   }
-  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N, kseg, lda,
-                                                                             ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, overwrite ? 1 : 0,
-                                                                             gu_f);
+  for (int i = 0; i < nseg; i++) sa.b[i] += cp.n1;
+  if (cp.tail == TAIL_256x128)
+    return launch<256, 128, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, N - cp.n1, kseg, lda,
+                                                                              ldb, ldc, 0, ab, bb, st, &sa, cp.n1, nullptr, ovw, gu_f);
+  return launch<128, 128, 64, 3, true, true, EPI_F32_ACC, PIPE_PLAIN, true>(sa.a[0], sa.b[0], C, nullptr, M, N - cp.n1, kseg, lda,
+                                                                             ldb, ldc, 0, ab, bb, st, &sa, cp.n1, nullptr, ovw, gu_f);
 }
 
 bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw) {
