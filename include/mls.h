@@ -182,7 +182,9 @@ int mls_stage_debug_read(mls_stage* s, int32_t tensor_id, int32_t layer, int32_t
  * more than 4096 launches are pending); enable = 0 stops it.  mls_stage_timing_read synchronises on the last
  * event, writes the accumulated milliseconds and launch counts per class into two HOST arrays of
  * MLS_TIMING_CLASSES entries (order: GEMM forward, GEMM data-gradient, GEMM weight-gradient, attention
- * forward, attention backward, RMSNorm, rotary, SwiGLU) and clears the accumulators.
+ * forward, attention backward, RMSNorm, rotary, SwiGLU) and clears the accumulators.  A step that runs fused into
+ * a neighbouring kernel (bf16 storage: the rotary steps, SwiGLU forward when ffn % 32 == 0) is counted with that
+ * kernel's class and leaves its own class at zero.
  * Errors: MLS_E_NULL, MLS_E_HIP. */
 #define MLS_TIMING_CLASSES 8
 int mls_stage_timing(mls_stage* s, int32_t enable);
