@@ -18,6 +18,8 @@
 // accumulators in AGPRs) or 8 (two per SIMD, 128x64 each, under 256 registers, so that one wavefront issues MFMAs
 // while the other waits at the barrier or for its fragments).  bf16 epilogues leave through an LDS staging pass
 // that turns the accumulator layout into whole-row 16-byte accesses.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -216,11 +218,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = (SEG ? segs.nseg : 1) * ((kpiece + BK - 1) / BK);
+  // Paired A tiles (forward projections: A is [row][k], 32 deep, i.e. 64 bytes of a row per k-tile).  Two consecutive
+  // k-tiles share their 128-byte lines; requested one iteration apart, the second request misses the CU's L1 again
+  // (48 KiB of lines pass through it per iteration) and every line of A comes from L2 twice.  Here the A tiles of
+  // an even / odd pair are requested back to back in one iteration (the L1 merges them: one L2 request per line),
+  // into a ring of 5 stages of their own; the B tiles keep their ring of NS = 4 and are requested every iteration.
+  constexpr bool PAIRA = !ATR && BTR && BK == 32 && PIPE == PIPE_SKEW && !SEG && NS == 4;
+  constexpr int RA = 5;  // stages of the A ring
+  if (!PAIRA) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; s++) {
+    for (int s = 0; s < NS - 1; s++) {
 #pragma unroll
-    for (int d = 0; d < LPT; d++) fire(d, s, s < nk);
-    advance();
+      for (int d = 0; d < LPT; d++) fire(d, s, s < nk);
+      advance();
+    }
   }
 
   // LDS reads per 16-wide k-substep and the MFMA : read interleave the scheduler is asked for
@@ -259,8 +270,80 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
       }
     }
   };
-  int stage = 0;
+  if constexpr (PAIRA) {
+    constexpr int NIB = BT_C::NI;
+    const uint32_t a_ring = lds0 + wave * (A_BYTES / NW), b_ring = lds0 + RA * A_BYTES + wave * (B_BYTES / NW);
+    // DMA instruction d of this wave for k-tile t (t >= nk: sent out of range, zero-fills a dead stage)
+    auto fire_a = [&](int d, int t, int st) {
+      dma16(ra, t < nk ? atr.voff(d, t * BK, K, lda) : OOB, a_ring + st * A_BYTES + d * 1024);
+    };
+    auto fire_b = [&](int d, int t, int st) {
+      dma16(rb, t < nk ? btc.voff(d, t * BK, K, ldb) : OOB, b_ring + st * B_BYTES + d * 1024);
+    };
+    auto lfrag2 = [&](int sta, int stb, int kk, int buf) {
+      const unsigned char* sa = smem + sta * A_BYTES;
+      const unsigned char* sb = smem + RA * A_BYTES + stb * B_BYTES;
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[buf][i] = AT_R::frag(sa, wm + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[buf][j] = BT_C::frag(sb, wn + j * 32, kk, lane);
+    };
+    // prologue, in this order: A0 B0 A1 B1 A2 B2 A3
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+#pragma unroll
+      for (int d = 0; d < NIA; d++) fire_a(d, t, t);
+      if (t < 3) {
+#pragma unroll
+        for (int d = 0; d < NIB; d++) fire_b(d, t, t);
+      }
+    }
+    wait_vmcnt<2 * (NIA + NIB) + NIA>();  // tile 0 has landed
+    __syncthreads();
+    lfrag2(0, 0, 0, 0);
+    int sa_cur = 0, sb_cur = 0;  // ring positions of tile kt
+    // one k-tile; ODD iterations request B(kt+3), A(kt+3), A(kt+4), even ones only B(kt+3)
+    auto iteration = [&](int kt, auto ODD) {
+      constexpr bool odd = decltype(ODD)::value;
+      // this wave's part of tile kt+1 has landed: behind it in the queue are, for an even kt, B(kt+2) A(kt+2) A(kt+3),
+      // for an odd kt, A(kt+2) B(kt+2)
+      if (odd) wait_vmcnt<NIA + NIB>(); else wait_vmcnt<2 * NIA + NIB>();
+      __syncthreads();  // ... everyone's has; the reads of tile kt-1 are retired
+      const int sa_n = sa_cur + 1 == RA ? 0 : sa_cur + 1, sb_n = sb_cur + 1 == NS ? 0 : sb_cur + 1;
+      const int sb3 = sb_cur == 0 ? NS - 1 : sb_cur - 1;                  // (kt + 3) % 4 == (kt - 1) % 4
+      const int sa3 = sa_cur + 3 >= RA ? sa_cur + 3 - RA : sa_cur + 3;    // (kt + 3) % 5
+      const int sa4 = sa_cur == 0 ? RA - 1 : sa_cur - 1;                  // (kt + 4) % 5 == (kt - 1) % 5
+      constexpr int NF = odd ? NIB + 2 * NIA : NIB, SLOTS = KS * TM;
+      auto fire_n = [&](int n) {  // the n-th request of this iteration
+        if (n < NIB) fire_b(n, kt + 3, sb3);
+        else if (n < NIB + NIA) fire_a(n - NIB, kt + 3, sa3);
+        else fire_a(n - NIB - NIA, kt + 4, sa4);
+      };
+#pragma unroll
+      for (int kk = 0; kk < KS; kk++) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk + 1 < KS) lfrag2(sa_cur, sb_cur, kk + 1, (kk + 1) & 1); else lfrag2(sa_n, sb_n, 0, 0);
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          const int slot = kk * TM + i;
+#pragma unroll
+          for (int n = slot * NF / SLOTS; n < (slot + 1) * NF / SLOTS; n++) fire_n(n);
+#pragma unroll
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+        }
+        interleave_hint();
+      }
+      sa_cur = sa_n;
+      sb_cur = sb_n;
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+      iteration(kt, std::false_type{});
+      if (kt + 1 < nk) iteration(kt + 1, std::true_type{});
+    }
+  } else
   if (PIPE == PIPE_SKEW) {
+    int stage = 0;
     // Skewed pipeline (needs NS >= 3 and an even number of substeps): the barrier at the top of iteration kt
     // publishes tile kt+1, so the first fragments of tile kt+1 are fetched during the last substep of tile kt
     // and no LDS latency is exposed behind the barrier.
@@ -285,6 +368,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
       stage = nstage;
     }
   } else {
+    int stage = 0;
     for (int kt = 0; kt < nk; kt++) {
       // tile kt has landed once at most the loads of the NS-2 younger tiles are still in flight
       wait_vmcnt<(NS - 2) * LPT>();
@@ -459,7 +543,9 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
                   int64_t ldb, int64_t ldc, int64_t ldr, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st,
                   const SegArgs* segs = nullptr, int col0 = 0, void* X = nullptr, int64_t ldx = 0, int xf = 0,
                   const RopeArgs* rope = nullptr) {
-  constexpr int LDS = NS * (BM + BN) * BK * 2;
+  // (the forward form keeps its A tiles in a ring of 5 stages beside the NS stages of B: see PAIRA in the kernel)
+  constexpr bool PAIRA = !ATR && BTR && BK == 32 && PIPE == PIPE_SKEW && !SEG && NS == 4;
+  constexpr int LDS = PAIRA ? (5 * BM + NS * BN) * BK * 2 : NS * (BM + BN) * BK * 2;
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;
