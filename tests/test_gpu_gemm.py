@@ -7,7 +7,9 @@ from tests.helpers import rel_err, to_host64
 pytestmark = pytest.mark.gpu
 
 SHAPES = [(256, 768, 256), (256, 1376, 256), (256, 256, 688), (392, 520, 328), (8, 8, 8), (1024, 2048, 512),
-          (4096, 4096, 1024), (520, 4104, 264), (4096, 22016, 136)]
+          (4096, 4096, 1024), (520, 4104, 264), (4096, 22016, 136),
+          # tiling plans: whole rounds of 256x256 tiles + a 128x128 tail; 256x128 tiles only; an odd number of k-tiles
+          (4096, 5120, 264), (2048, 4096, 200), (4096, 4096, 96)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
