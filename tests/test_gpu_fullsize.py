@@ -51,12 +51,14 @@ def test_full_configuration_all_layers_all_microbatches(name):
     micro-batches: 1e-4.
     (2) Properties that hold at any size: y and dX of every micro-batch are bitwise what a one-at-a-time execution
     gives, and the batched weight gradient equals the sum of the single ones to fp32 summation order.
-    (3) Parity at full depth (7B only: the oracle needs a minute for it): micro-batch 0 through all four layers
-    against the oracle in storage-rounded mode (y, dX, and the gradients of a run that holds only micro-batch 0).
-    The 1e-2 bound is a one-layer bound: bf16 storage noise grows with depth, and the oracle's own storage-rounded
-    mode stands 1.04e-2 (y), 1.41e-2 (dX) and 2.63e-2 (largest gradient distance, gamma1 / w_qkv of the last layer)
-    from its exact mode on these very inputs (measured on the CPU, oracle only).  Two bf16 executions that round
-    in different orders sit at that distance from each other too, so the bounds here are 1.5 times those floors."""
+    (3) Parity at full depth (7B: four layers; 70B shard: three layers with grouped KV heads; 13B is left out, its
+    oracle pass takes too long): micro-batch 0 through all layers against the oracle in storage-rounded mode (y,
+    dX, and the gradients of a run that holds only micro-batch 0).  The 1e-2 bound is a one-layer bound: bf16 storage
+    noise grows with depth, and the oracle's own storage-rounded mode stands, for 7B, 1.04e-2 (y), 1.41e-2 (dX)
+    and 2.63e-2 (largest gradient distance, gamma1 / w_qkv of the last layer) from its exact mode on these very
+    inputs, for the shard 1.55e-2 / 2.95e-2 / 4.72e-2 (measured on the CPU, oracle only).  Two bf16 executions that
+    round in different orders sit at that distance from each other too, so the bounds here are 1.5 times those
+    floors."""
     import torch
     import paper_2410_13333_amd as mls
     from tests.helpers import to_device, to_host64
@@ -114,11 +116,14 @@ def test_full_configuration_all_layers_all_microbatches(name):
     del gsum, g1
     y0, dx0 = to_host64(ys[0]), to_host64(dx[0])
     st.close()
-    if name != "7b":
+    # bf16 depth floors: oracle storage-rounded mode against oracle exact mode on these inputs (CPU, oracle only)
+    floors = {"7b": (1.04e-2, 1.41e-2, 2.63e-2), "70b_tp4": (1.55e-2, 2.95e-2, 4.72e-2)}
+    if name not in floors:
         return
     t0 = time.time()
     rys, rdxs, rg = oracle_step(sh.with_(microbatches=1), 1001, 2001, 3001, [K], store=bf16_store)
     ey, ex = rel_err(y0, rys[0]), rel_err(dx0, rdxs[0])
     eg, errs = grad_errors(sh, g0, rg, K)
-    print(f"[7b 4 layers] vs stored oracle ({time.time() - t0:.1f} s): y={ey:.2e} dx={ex:.2e} grads(max)={eg:.2e}", flush=True)
-    assert ey <= 1.6e-2 and ex <= 2.1e-2 and eg <= 4e-2, (ey, ex, sorted(errs.items(), key=lambda kv: -kv[1])[:3])
+    print(f"[{name} {K} layers] vs stored oracle ({time.time() - t0:.1f} s): y={ey:.2e} dx={ex:.2e} grads(max)={eg:.2e}", flush=True)
+    fy, fx, fg = floors[name]
+    assert ey <= 1.5 * fy and ex <= 1.5 * fx and eg <= 1.5 * fg, (ey, ex, sorted(errs.items(), key=lambda kv: -kv[1])[:3])
