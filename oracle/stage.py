@@ -14,11 +14,12 @@ mathematics, so the oracle is the plain definition: the full S x S score matrix 
 is blocked, fused or reordered.  All arithmetic is fp64; callers pass values already rounded to the
 storage type when they model a bf16 run.
 
-Storage-rounded mode.  layer_forward / layer_backward take an optional `store(name, tensor)` hook that is
-applied to every tensor the stage writes to memory in its storage type (the names are listed at _STORE_POINTS).
-With the default (identity) the oracle is the exact fp64 function that the pins below fix.  With a hook that
-rounds to bf16 it states what a path that keeps every intermediate tensor in bf16, and is otherwise exact,
-computes; the arithmetic between two stores is the same fp64 code either way.
+Rounding hook.  The layer functions take an optional `store(name, tensor)` hook, called at every named
+intermediate tensor of the definition (ROUNDING_POINTS).  With the default (identity) the oracle is the exact fp64
+function that the pins below fix, and that is what parity is judged against.  A hook that rounds some of the names
+to bf16 states what an otherwise exact path computes when it keeps those tensors in bf16; the tests use it only to
+measure, on the CPU, how far such roundings alone move a result (one name at a time, or a set of names), never as
+the function the library has to match.  The arithmetic between two hook calls is the same fp64 code either way.
 
 Parity pins (tests/test_oracle_*.py): central finite differences on every parameter and on dX, softmax
 rows summing to one, causality, RoPE norm preservation / relative-position property, the RMSNorm closed
@@ -28,6 +29,10 @@ gradient accumulation and layer composition.
 from __future__ import annotations
 
 import numpy as np
+
+
+def _identity(name, t):
+    return t
 
 # ---------------------------------------------------------------- RMSNorm
 
@@ -68,10 +73,12 @@ def rope_apply(u, angle, sign=1.0):
 # ---------------------------------------------------------------- attention
 
 
-def attention_fwd(q, k, v):
+def attention_fwd(q, k, v, store=None):
     """Causal softmax attention with grouped KV heads.
     q: [b,S,n_q,d], k,v: [b,S,n_kv,d].  Query head hq reads KV head hq // (n_q/n_kv).
-    Returns o [b,S,n_q,d] and the probabilities p [b,n_q,S,S] (zero above the diagonal)."""
+    Returns o [b,S,n_q,d] and the probabilities p [b,n_q,S,S] (zero above the diagonal).
+    store: optional rounding hook (see the module header); "p" is the probability operand of the product with V."""
+    st = store or _identity
     b, S, nq, d = q.shape
     g = nq // k.shape[2]
     mask = np.tril(np.ones((S, S), dtype=bool))
@@ -85,14 +92,17 @@ def attention_fwd(q, k, v):
             e = np.exp(s - s.max(axis=1, keepdims=True))      # masked entries are exactly 0
             pr = e / e.sum(axis=1, keepdims=True)
             p[bi, hq] = pr
-            o[bi, :, hq, :] = pr @ v[bi, :, hk, :]
+            o[bi, :, hq, :] = st("p", pr) @ v[bi, :, hk, :]
     return o, p
 
 
-def attention_bwd(do, q, k, v, p):
+def attention_bwd(do, q, k, v, p, store=None):
     """Reverse mode of attention_fwd.  dV_j += sum_i p_ij dO_i; dp_ij = dO_i . V_j;
     ds_ij = p_ij (dp_ij - sum_j' p_ij' dp_ij'); dQ_i = sum_j ds_ij K_j / sqrt(d);
-    dK_j += sum_i ds_ij Q_i / sqrt(d), the KV gradients summed over the query heads of a group."""
+    dK_j += sum_i ds_ij Q_i / sqrt(d), the KV gradients summed over the query heads of a group.
+    store: optional rounding hook; "p_dv" is the probability operand of the dV product, "ds" the score-gradient
+    operand of the dQ and dK products."""
+    st = store or _identity
     b, S, nq, d = q.shape
     g = nq // k.shape[2]
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
@@ -101,9 +111,9 @@ def attention_bwd(do, q, k, v, p):
             hk = hq // g
             pr = p[bi, hq]
             dO = do[bi, :, hq, :]
-            dv[bi, :, hk, :] += pr.T @ dO
+            dv[bi, :, hk, :] += st("p_dv", pr).T @ dO
             dp = dO @ v[bi, :, hk, :].T
-            ds = pr * (dp - np.sum(pr * dp, axis=1, keepdims=True))
+            ds = st("ds", pr * (dp - np.sum(pr * dp, axis=1, keepdims=True)))
             dq[bi, :, hq, :] = ds @ k[bi, :, hk, :] / np.sqrt(d)
             dk[bi, :, hk, :] += ds.T @ q[bi, :, hq, :] / np.sqrt(d)
     return dq, dk, dv
@@ -127,15 +137,13 @@ def swiglu_bwd(dz, g, u):
 
 # ---------------------------------------------------------------- one decoder layer
 
-# tensors written to memory by one layer, in order: forward, then backward ("_pre" = before the rotary step,
-# which rewrites the q and k parts in place and leaves v as it is)
-_STORE_POINTS = ("a", "qkv_pre", "qkv", "o", "h", "b", "gu", "z", "y",
-                 "dz", "dgu", "db", "dh", "dc", "dqkv_pre", "dqkv", "da", "dx")
-
-
-def _identity(name, t):
-    return t
-
+# Rounding points: every intermediate tensor of one layer's definition has a name, in order forward then
+# backward.  "_pre" = before the rotary step (which changes q and k, not v); "gu" is what the forward's SwiGLU
+# consumes, "gu_kept" what the backward's SwiGLU derivative consumes; "p", "p_dv", "ds" are the matrix operands
+# inside the attention (see attention_fwd / attention_bwd).  A hook sees (name, tensor) and returns the tensor
+# its consumers read.
+ROUNDING_POINTS = ("a", "qk_pre", "v", "qk", "p", "o", "h", "b", "gu", "gu_kept", "z", "y",
+                   "dz", "dgu", "db", "dh", "dc", "p_dv", "ds", "dqk_pre", "dv", "dqk", "da", "dx")
 
 
 def layer_forward(x, w, sh, store=None):
@@ -148,22 +156,22 @@ def layer_forward(x, w, sh, store=None):
     X = x.reshape(b * S, h)
     A, r1 = rmsnorm_fwd(X, w["gamma1"], sh.rms_eps)
     A = st("a", A)
-    QKV = st("qkv_pre", A @ w["w_qkv"])
+    QKV = A @ w["w_qkv"]
     ang = rope_angles(S, d, sh.rope_base)
-    qk = st("qkv", rope_apply(QKV[:, :qd + kvd].reshape(b, S, nq + nkv, d), ang))
+    qk = st("qk", rope_apply(st("qk_pre", QKV[:, :qd + kvd]).reshape(b, S, nq + nkv, d), ang))
     q, k = qk[:, :, :nq, :], qk[:, :, nq:, :]
-    v = QKV[:, qd + kvd:].reshape(b, S, nkv, d)
-    o, p = attention_fwd(q, k, v)
+    v = st("v", QKV[:, qd + kvd:]).reshape(b, S, nkv, d)
+    o, p = attention_fwd(q, k, v, store)
     o = st("o", o)
     C = o.reshape(b * S, qd)
     H = st("h", X + C @ w["w_o"])
     B, r2 = rmsnorm_fwd(H, w["gamma2"], sh.rms_eps)
     B = st("b", B)
     GU = st("gu", B @ w["w_gu"])
-    G, U = GU[:, :f], GU[:, f:]
-    Z = st("z", swiglu_fwd(G, U))
+    Z = st("z", swiglu_fwd(GU[:, :f], GU[:, f:]))
     Y = st("y", H + Z @ w["w_d"])
-    cache = dict(X=X, A=A, r1=r1, q=q, k=k, v=v, p=p, C=C, H=H, B=B, r2=r2, G=G, U=U, Z=Z, ang=ang)
+    GUk = st("gu_kept", GU)
+    cache = dict(X=X, A=A, r1=r1, q=q, k=k, v=v, p=p, C=C, H=H, B=B, r2=r2, G=GUk[:, :f], U=GUk[:, f:], Z=Z, ang=ang)
     return Y.reshape(b, S, h), cache
 
 
@@ -186,10 +194,10 @@ def layer_backward(dy, w, cache, sh, store=None):
     dH = st("dh", dY + dHn)
     dC = st("dc", dH @ w["w_o"].T)
     g["w_o"] = c["C"].T @ dH
-    dq, dk, dv = attention_bwd(dC.reshape(b, S, nq, d), c["q"], c["k"], c["v"], c["p"])
-    dq, dk, dv = st("dqkv_pre", dq), st("dqkv_pre", dk), st("dqkv_pre", dv)
-    dq = st("dqkv", rope_apply(dq, c["ang"], sign=-1.0))
-    dk = st("dqkv", rope_apply(dk, c["ang"], sign=-1.0))
+    dq, dk, dv = attention_bwd(dC.reshape(b, S, nq, d), c["q"], c["k"], c["v"], c["p"], store)
+    dq, dk, dv = st("dqk_pre", dq), st("dqk_pre", dk), st("dv", dv)
+    dq = st("dqk", rope_apply(dq, c["ang"], sign=-1.0))
+    dk = st("dqk", rope_apply(dk, c["ang"], sign=-1.0))
     dQKV = np.concatenate([dq.reshape(b * S, qd), dk.reshape(b * S, kvd), dv.reshape(b * S, kvd)], axis=1)
     dA = st("da", dQKV @ w["w_qkv"].T)
     g["w_qkv"] = c["A"].T @ dQKV

@@ -33,10 +33,21 @@ def storage_bits(t):
     return t.cpu().numpy()
 
 
-def bf16_store(name, t):
-    """store hook of the oracle's storage-rounded mode: every stored tensor is rounded once to bf16."""
+def round_bf16(t):
     _, v = synth.round_to_storage(np.ascontiguousarray(t).reshape(-1), "bf16")
     return v.reshape(t.shape)
+
+
+def rounding_hook(names):
+    """Hook for the oracle that rounds the named intermediate tensors (oracle.stage.ROUNDING_POINTS) to bf16 and
+    leaves the others exact.  A CPU measuring device: how far do these roundings alone move a result."""
+    names = frozenset(names)
+    return lambda name, t: round_bf16(t) if name in names else t
+
+
+def bf16_store(name, t):
+    """Hook that rounds every named intermediate tensor to bf16."""
+    return round_bf16(t)
 
 
 def oracle_step(sh, wseed, xseed, dyseed, ks, params64=None, store=None):

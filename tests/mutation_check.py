@@ -27,11 +27,11 @@ M = [
  ("stage.py", "            hk = hq // g\n            s = q", "            hk = hq % k.shape[2]\n            s = q"),
  ("stage.py", "mask = np.tril(np.ones((S, S), dtype=bool))", "mask = np.tril(np.ones((S, S), dtype=bool), -1) | np.eye(S, dtype=bool)[0:1].T.repeat(S, 1)"),
  ("stage.py", "mask = np.tril(np.ones((S, S), dtype=bool))", "mask = np.ones((S, S), dtype=bool)"),
- ("stage.py", "o[bi, :, hq, :] = pr @ v[bi, :, hk, :]", "o[bi, :, hq, :] = pr @ k[bi, :, hk, :]"),
- ("stage.py", "dv[bi, :, hk, :] += pr.T @ dO", "dv[bi, :, hk, :] = pr.T @ dO"),
- ("stage.py", "dv[bi, :, hk, :] += pr.T @ dO", "dv[bi, :, hk, :] += pr @ dO"),
- ("stage.py", "ds = pr * (dp - np.sum(pr * dp", "ds = pr * (dp + np.sum(pr * dp"),
- ("stage.py", "ds = pr * (dp - np.sum(pr * dp, axis=1, keepdims=True))", "ds = pr * dp"),
+ ("stage.py", "o[bi, :, hq, :] = st(\"p\", pr) @ v[bi, :, hk, :]", "o[bi, :, hq, :] = st(\"p\", pr) @ k[bi, :, hk, :]"),
+ ("stage.py", "dv[bi, :, hk, :] += st(\"p_dv\", pr).T @ dO", "dv[bi, :, hk, :] = st(\"p_dv\", pr).T @ dO"),
+ ("stage.py", "dv[bi, :, hk, :] += st(\"p_dv\", pr).T @ dO", "dv[bi, :, hk, :] += st(\"p_dv\", pr) @ dO"),
+ ("stage.py", "ds = st(\"ds\", pr * (dp - np.sum(pr * dp", "ds = st(\"ds\", pr * (dp + np.sum(pr * dp"),
+ ("stage.py", "ds = st(\"ds\", pr * (dp - np.sum(pr * dp, axis=1, keepdims=True)))", "ds = st(\"ds\", pr * dp)"),
  ("stage.py", "dq[bi, :, hq, :] = ds @ k[bi, :, hk, :] / np.sqrt(d)", "dq[bi, :, hq, :] = ds @ k[bi, :, hk, :]"),
  ("stage.py", "dk[bi, :, hk, :] += ds.T @ q[bi, :, hq, :] / np.sqrt(d)", "dk[bi, :, hk, :] = ds.T @ q[bi, :, hq, :] / np.sqrt(d)"),
  ("stage.py", "dk[bi, :, hk, :] += ds.T @ q[bi, :, hq, :] / np.sqrt(d)", "dk[bi, :, hk, :] += ds @ q[bi, :, hq, :] / np.sqrt(d)"),
@@ -42,7 +42,8 @@ M = [
  ("stage.py", "return dz * u * s * (1.0 + g * (1.0 - s)), dz * g * s", "return dz * u * s * (1.0 - g * (1.0 - s)), dz * g * s"),
  ("stage.py", 'H = st("h", X + C @ w["w_o"])', 'H = st("h", C @ w["w_o"])'),
  ("stage.py", 'Y = st("y", H + Z @ w["w_d"])', 'Y = st("y", X + Z @ w["w_d"])'),
- ("stage.py", "G, U = GU[:, :f], GU[:, f:]\n    Z", "U, G = GU[:, :f], GU[:, f:]\n    Z"),
+ ("stage.py", "swiglu_fwd(GU[:, :f], GU[:, f:])", "swiglu_fwd(GU[:, f:], GU[:, :f])"),
+ ("stage.py", "G=GUk[:, :f], U=GUk[:, f:]", "U=GUk[:, :f], G=GUk[:, f:]"),
  ("stage.py", "q, k = qk[:, :, :nq, :], qk[:, :, nq:, :]", "q, k = qk[:, :, :nq, :], QKV[:, qd:qd + kvd].reshape(b, S, nkv, d)"),
  ("stage.py", 'B, r2 = rmsnorm_fwd(H, w["gamma2"], sh.rms_eps)', 'B, r2 = rmsnorm_fwd(H, w["gamma1"], sh.rms_eps)'),
  ("stage.py", 'dH = st("dh", dY + dHn)', 'dH = st("dh", dHn)'),
@@ -52,8 +53,8 @@ M = [
  ("stage.py", 'g["w_gu"] = c["B"].T @ dGU', 'g["w_gu"] = c["H"].T @ dGU'),
  ("stage.py", 'g["w_o"] = c["C"].T @ dH', 'g["w_o"] = c["C"].T @ dY'),
  ("stage.py", 'g["w_qkv"] = c["A"].T @ dQKV', 'g["w_qkv"] = c["X"].T @ dQKV'),
- ("stage.py", 'dq = st("dqkv", rope_apply(dq, c["ang"], sign=-1.0))', 'dq = st("dqkv", rope_apply(dq, c["ang"], sign=1.0))'),
- ("stage.py", 'dk = st("dqkv", rope_apply(dk, c["ang"], sign=-1.0))', 'dk = st("dqkv", dk)'),
+ ("stage.py", 'dq = st("dqk", rope_apply(dq, c["ang"], sign=-1.0))', 'dq = st("dqk", rope_apply(dq, c["ang"], sign=1.0))'),
+ ("stage.py", 'dk = st("dqk", rope_apply(dk, c["ang"], sign=-1.0))', 'dk = st("dqk", dk)'),
  ("stage.py", 'dHn, g["gamma2"] = rmsnorm_bwd(dB, c["H"], w["gamma2"], c["r2"])', 'dHn, g["gamma2"] = rmsnorm_bwd(dB, c["H"], w["gamma2"], c["r1"])'),
  ("stage.py", "    for l in range(k - 1, -1, -1):\n        d, grads[l]", "    for l in range(k):\n        d, grads[l]"),
  ("stage.py", "                total[l][n] += grads[l][n]", "                total[l][n] = grads[l][n]"),

@@ -366,7 +366,7 @@ def test_layer_against_library_routines_and_autograd():
         assert rel(og[n], tw[n].grad.numpy()) < 1e-12, n
 
 
-def test_storage_rounded_mode_is_the_same_function_with_rounded_stores():
+def test_rounding_hook_sees_every_named_tensor_and_identity_changes_nothing():
     from tests.helpers import bf16_store
     sh = TINY
     W = _weights(sh, 50)
@@ -381,9 +381,10 @@ def test_storage_rounded_mode_is_the_same_function_with_rounded_stores():
     dx0, g0 = O.stage_backward(dy, W, c0, sh)
     dx1, g1 = O.stage_backward(dy, W, c1, sh, store=spy)
     assert np.array_equal(y0, y1) and np.array_equal(dx0, dx1) and np.array_equal(g0[1]["w_qkv"], g1[1]["w_qkv"])
-    fwd = ["a", "qkv_pre", "qkv", "o", "h", "b", "gu", "z", "y"]
-    bwd = ["dz", "dgu", "db", "dh", "dc", "dqkv_pre", "dqkv_pre", "dqkv_pre", "dqkv", "dqkv", "da", "dx"]
-    assert seen == fwd * 2 + bwd * 2 and set(seen) == set(O._STORE_POINTS)
+    heads = sh.micro_batch * sh.n_q_heads
+    fwd = ["a", "qk_pre", "qk", "v"] + ["p"] * heads + ["o", "h", "b", "gu", "z", "y", "gu_kept"]
+    bwd = ["dz", "dgu", "db", "dh", "dc"] + ["p_dv", "ds"] * heads + ["dqk_pre", "dqk_pre", "dv", "dqk", "dqk", "da", "dx"]
+    assert seen == fwd * 2 + bwd * 2 and set(seen) == set(O.ROUNDING_POINTS)
     y2, c2 = O.stage_forward(x, W, sh, store=bf16_store)
     dx2, g2 = O.stage_backward(dy, W, c2, sh, store=bf16_store)
     rel = lambda a, b: np.linalg.norm(a - b) / np.linalg.norm(b)
