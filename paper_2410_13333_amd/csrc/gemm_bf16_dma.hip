@@ -26,8 +26,9 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-// EPI_ROPE: C = acc rounded to bf16, then the head vectors in columns below rot_cols rotated by the rotary angle of
-// their row's position (row % seq), pairs (i, i + head_dim/2); the remaining columns (v) are stored as they are.
+// EPI_ROPE: the head vectors in columns below rot_cols are rotated by the rotary angle of their row's position
+// (row % seq), pairs (i, i + head_dim/2), in fp32 on the accumulators, and rounded to bf16 once; the remaining
+// columns (v) are stored as they are.
 // Epilogues.  EPI_BF16: C = acc (+ R), bf16.  EPI_F32_ACC: C += acc, fp32 (C = acc when `ldx` != 0); with `xf` > 0
 // the columns are the gate/up-interleaved order and are written to their public places (see gu_public_col).  EPI_SWIGLU: N = 2f
 // interleaved columns [gate | up]; C receives both (bf16) and X[row][f] their SwiGLU product.  (The SwiGLU backward
@@ -441,6 +442,62 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
         }
         wave_lds_sync();
       }
+      if constexpr (EPI == EPI_ROPE) {
+        // Rotation on the fp32 accumulators.  A head of 64 columns is this wave's two 32-column tiles: the partner of
+        // a value sits in the same lane, in the other tile.  A head of 128 columns spans this wave's 64 columns and
+        // those of the wave next to it along N (wave ^ 2): the waves exchange their fp32 rows through LDS behind the
+        // bf16 staging areas (8 KiB per wave, 16-byte chunks XOR-swizzled by row).
+        const bool wide = rope.head_dim == 128;
+        const bool rot = col0 + n0 + wn < rope.rot_cols;  // whole heads: uniform over the wave
+        const int d2 = rope.head_dim >> 1;
+        unsigned char* fx = smem + 64 * 1024;
+        auto fx_at = [&](int w, int chunk) { return fx + w * 8192 + r32 * 256 + ((chunk ^ (r32 & 15)) << 4); };
+        if (wide) {
+          if (rot) {
+#pragma unroll
+            for (int q = 0; q < TN * 4; q++) {
+              const int j = q >> 2, g = q & 3;
+              *reinterpret_cast<float4*>(fx_at(wave, j * 8 + 2 * g + hi)) =
+                  make_float4(acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+            }
+          }
+          __syncthreads();
+        }
+        if (rot) {
+          const int row = row0 + r32;
+          const int64_t at = int64_t((row < M ? row : 0) % rope.seq) * d2 + hi * 4;
+          const bool first = !((wave >> 1) & 1);  // wide: this wave holds the first halves of its pairs
+#pragma unroll
+          for (int g = 0; g < 4; g++) {
+            if (wide) {
+#pragma unroll
+              for (int j = 0; j < TN; j++) {
+                const float4 pv = *reinterpret_cast<const float4*>(fx_at(wave ^ 2, j * 8 + 2 * g + hi));
+                const float4 cs = *reinterpret_cast<const float4*>(rope.cos_tab + at + j * 32 + 8 * g);
+                const float4 sn = *reinterpret_cast<const float4*>(rope.sin_tab + at + j * 32 + 8 * g);
+                const float pp[4] = {pv.x, pv.y, pv.z, pv.w}, c[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                  const float own = acc[i][j][g * 4 + e];
+                  // first half: u1 c - u2 s with u1 own, u2 partner; second half: u1 s + u2 c with u1 partner, u2 own
+                  acc[i][j][g * 4 + e] = first ? own * c[e] - pp[e] * sv[e] : pp[e] * sv[e] + own * c[e];
+                }
+              }
+            } else {
+              const float4 cs = *reinterpret_cast<const float4*>(rope.cos_tab + at + 8 * g);
+              const float4 sn = *reinterpret_cast<const float4*>(rope.sin_tab + at + 8 * g);
+              const float c[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+              for (int e = 0; e < 4; e++) {
+                const float u1 = acc[i][0][g * 4 + e], u2 = acc[i][1][g * 4 + e];
+                acc[i][0][g * 4 + e] = u1 * c[e] - u2 * sv[e];
+                acc[i][1][g * 4 + e] = u1 * sv[e] + u2 * c[e];
+              }
+            }
+          }
+        }
+        if (wide) __syncthreads();  // the partner has read this wave's rows: the next 32 rows may overwrite them
+      }
       // combine in the accumulator layout, in place
       constexpr int ZRB = CW, ZNCH = ZRB / 16, ZRPL = ZRB < 256 ? 256 / ZRB : 1;  // SwiGLU product: half as many columns, staged behind the 8 KiB
       unsigned char* wz = ws + 32 * RB;
@@ -462,11 +519,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
         *reinterpret_cast<uint2*>(p) = o;
         if (EPI == EPI_SWIGLU && !(j & 1)) {
           // 32-column blocks alternate gate, up: tile j (even) holds the gates of the ups in tile j + 1.  The
-          // product is formed from the stored (rounded) values, like a separate kernel reading them back.
+          // product is formed from the fp32 accumulators and rounded once.
           float z[4];
 #pragma unroll
           for (int e = 0; e < 4; e++) {
-            const float gr = round_bf16(v[e]), ur = round_bf16(acc[i][j | 1][g * 4 + e]);
+            const float gr = v[e], ur = acc[i][j | 1][g * 4 + e];
             z[e] = gr * sigmoidf_(gr) * ur;
           }
           uint2 zo;
@@ -475,44 +532,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
           const int zc = 4 * (j >> 1) + g;
           *reinterpret_cast<uint2*>(wz + r32 * ZRB + ((zc ^ ((r32 / ZRPL) & (ZNCH - 1))) << 4) + hi * 8) = zo;
         }
-      }
-      if (EPI == EPI_ROPE) {
-        // A head of 128 columns spans this wave's 64 and those of the wave next to it along N (wave ^ 2): the
-        // partner's staged rows are read once every wave has staged its own.  A head of 64 columns is the wave's own.
-        const bool wide = rope.head_dim == 128;
-        if (wide) __syncthreads(); else wave_lds_sync();
-        const bool rot = col0 + n0 + wn < rope.rot_cols;  // whole heads: uniform over the wave
-        const unsigned char* pw = wide ? smem + (wave ^ 2) * (64 * 1024 / NW) : ws;
-        const int pch = wide ? cch : cch ^ 4;                        // the partner's chunk of the same row
-        const bool first = wide ? !((wave >> 1) & 1) : cch < 4;      // this lane holds the first halves of its pairs
-        const int d2 = rope.head_dim >> 1, i0 = (wide ? cch : cch & 3) * 8;
-#pragma unroll
-        for (int t = 0; t < NT; t++) {
-          const int lrow = t * RPI + crow, row = row0 + lrow;
-          uint4 o = *reinterpret_cast<const uint4*>(stage_at(lrow, cch));
-          if (rot && row < M && col_ok) {
-            const uint4 q = *reinterpret_cast<const uint4*>(pw + lrow * RB + ((pch ^ ((lrow / RPL) & (NCH - 1))) << 4));
-            const int64_t at = int64_t(row % rope.seq) * d2 + i0;
-            float cs[8], sn[8];
-            load8(rope.cos_tab + at, cs);
-            load8(rope.sin_tab + at, sn);
-            const uint32_t ow[4] = {o.x, o.y, o.z, o.w}, qw[4] = {q.x, q.y, q.z, q.w};
-            uint32_t r[4];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const float a0 = __uint_as_float(ow[e] << 16), a1 = __uint_as_float(ow[e] & 0xffff0000u);
-              const float b0 = __uint_as_float(qw[e] << 16), b1 = __uint_as_float(qw[e] & 0xffff0000u);
-              // first half: u1 c - u2 s with u1 own, u2 partner; second half: u1 s + u2 c with u1 partner, u2 own
-              const float v0 = first ? a0 * cs[2 * e] - b0 * sn[2 * e] : b0 * sn[2 * e] + a0 * cs[2 * e];
-              const float v1 = first ? a1 * cs[2 * e + 1] - b1 * sn[2 * e + 1] : b1 * sn[2 * e + 1] + a1 * cs[2 * e + 1];
-              r[e] = pack_bf16x2(v0, v1);
-            }
-            o = make_uint4(r[0], r[1], r[2], r[3]);
-          }
-          if (row < M && col_ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(Cv) + int64_t(row) * ldc + ccol) = o;
-        }
-        if (wide) __syncthreads(); else wave_lds_sync();
-        continue;
       }
       wave_lds_sync();
 #pragma unroll
@@ -546,6 +565,9 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
   // (the forward form keeps its A tiles in a ring of 5 stages beside the NS stages of B: see PAIRA in the kernel)
   constexpr bool PAIRA = !ATR && BTR && BK == 32 && PIPE == PIPE_SKEW && !SEG && NS == 4;
   constexpr int LDS = PAIRA ? (5 * BM + NS * BN) * BK * 2 : NS * (BM + BN) * BK * 2;
+  // the rotary epilogue keeps 8 KiB of fp32 rows per wavefront behind the 64 KiB of bf16 staging areas and pairs the
+  // two 32-column tiles of a wavefront
+  static_assert(EPI != EPI_ROPE || (LDS >= (64 + 8 * NW) * 1024 && BN / (NW / 2) == 64), "rotary epilogue: LDS or wave tile");
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;

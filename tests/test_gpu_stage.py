@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import synth
-from tests.helpers import (bf16_store, gpu_step, grad_errors, oracle_step, rel_err, storage_bits, to_device,
+from tests.helpers import (gpu_step, grad_errors, oracle_step, rel_err, round_bf16, storage_bits, to_device,
                            to_host64)
 
 pytestmark = pytest.mark.gpu
@@ -24,16 +24,11 @@ GQA128 = synth.StageShape(hidden=256, n_q_heads=4, n_kv_heads=1, head_dim=128, f
                           layers=1, microbatches=2)
 
 
-TOL_STORED = 1e-2   # bf16 run against the oracle in storage-rounded mode (every op consumes bf16-rounded inputs)
-
-
 def _check(sh, ks, tol, interleave=False):
     ys, dxs, g, st = gpu_step(sh, 1000, 2000, 3000, ks, interleave)
     assert st.inflight == 0
     st.close()
-    refs = [("exact", tol, oracle_step(sh, 1000, 2000, 3000, ks))]
-    if sh.dtype == "bf16":
-        refs.append(("stored", TOL_STORED, oracle_step(sh, 1000, 2000, 3000, ks, store=bf16_store)))
+    refs = [("exact", tol, oracle_step(sh, 1000, 2000, 3000, ks))]     # the exact fp64 oracle is the only bar
     for kind, t, (rys, rdxs, rg) in refs:
         ey = max(rel_err(ys[mb], rys[mb]) for mb in range(len(ks)))
         ex = max(rel_err(dxs[mb], rdxs[mb]) for mb in range(len(ks)))
@@ -281,11 +276,12 @@ def test_token_counts_that_are_not_multiples_of_eight(seq, mb):
 @pytest.mark.parametrize("nq,nkv,d,seq,mb", [(30, 2, 128, 4096, 1), (60, 4, 64, 4096, 1), (6, 2, 128, 1000, 3),
                                               (6, 2, 64, 1000, 3)])
 def test_rotary_epilogue_of_the_qkv_projection(nq, nkv, d, seq, mb):
-    """q|k|v after the rotary step, read back from the stash, against RMSNorm -> projection -> rotation in fp64 with
-    the same bf16 storage points.  The shapes take the projection through every tiling of its kernel: (30, 2, 128)
-    and (60, 4, 64) at 4096 tokens give 17 column tiles of 256 = a full round of 256x256 tiles plus a 256x128 tail
-    launch; 3000 tokens x 1280 / 640 columns run on the 128x128 tiles with ragged rows.  The positions restart
-    with every sequence of the micro-batch."""
+    """q|k|v after the rotary step, read back from the stash, against RMSNorm -> projection -> rotation in fp64 where
+    only what the matrix unit needs is rounded to bf16: the normalised input before the projection and q|k|v once, after
+    the rotation.  The shapes take the projection through every tiling of its kernel: (30, 2, 128) and (60, 4, 64) at
+    4096 tokens give 17 column tiles of 256 = a full round of 256x256 tiles plus a 256x128 tail launch; 3000 tokens x
+    1280 / 640 columns run on the 128x128 tiles with ragged rows.  The positions restart with every sequence of the
+    micro-batch."""
     import paper_2410_13333_amd as mls
     import oracle.stage as O
     sh = synth.StageShape(hidden=256, n_q_heads=nq, n_kv_heads=nkv, head_dim=d, ffn=64, seq=seq, micro_batch=mb,
@@ -301,12 +297,15 @@ def test_rotary_epilogue_of_the_qkv_projection(nq, nkv, d, seq, mb):
     _, p64 = synth.make_params(sh, 1000)
     w = synth.split_params(sh, p64, 0)
     a, _ = O.rmsnorm_fwd(x.reshape(seq * mb, sh.hidden), w["gamma1"], sh.rms_eps)
-    pre = bf16_store("qkv_pre", bf16_store("a", a) @ w["w_qkv"])
+    pre = round_bf16(a) @ w["w_qkv"]
     qd, kvd = nq * d, nkv * d
     rot = O.rope_apply(pre[:, :qd + kvd].reshape(mb, seq, nq + nkv, d), O.rope_angles(seq, d, sh.rope_base))
-    ref = np.concatenate([bf16_store("qkv", rot).reshape(seq * mb, qd + kvd), pre[:, qd + kvd:]], axis=1)
+    ref = round_bf16(np.concatenate([rot.reshape(seq * mb, qd + kvd), pre[:, qd + kvd:]], axis=1))
+    # one rounding on each side; what is left are the elements whose fp32 and fp64 values round to different
+    # neighbours (a bf16 step is 2^-8 of the value, and the normalised input already differs that way now and then)
     for name, lo, hi in (("q", 0, qd), ("k", qd, qd + kvd), ("v", qd + kvd, qd + 2 * kvd)):
         e = rel_err(got[:, lo:hi], ref[:, lo:hi])
-        assert e <= 3e-3, (name, e)
+        print(f"[rotary epilogue nq={nq} d={d}] {name}: {e:.2e}")
+        assert e <= 2e-3, (name, e)
     # per-head check on the last head of k and the last rows: a wrong pairing or position would be O(1) there
-    assert rel_err(got[-64:, qd + kvd - d:qd + kvd], ref[-64:, qd + kvd - d:qd + kvd]) <= 3e-3
+    assert rel_err(got[-64:, qd + kvd - d:qd + kvd], ref[-64:, qd + kvd - d:qd + kvd]) <= 2e-3
