@@ -382,7 +382,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
       for (int kk = 0; kk < KS; kk++) {
         __builtin_amdgcn_sched_barrier(0);
         if (kk + 1 < KS) lfrag(sa, kk + 1, (kk + 1) & 1);
-        mfma_block(kk, pstage, prefetch, kk * DPK, (kk + 1) * DPK < LPT ? (kk + 1) * DPK : LPT);
+        // every request for the next tile goes out in the first substep, right behind the barrier that freed its
+        // stage: with two stages a request issued later in the k-step has less than a k-step to land
+        mfma_block(kk, pstage, prefetch, kk == 0 ? 0 : LPT, LPT);
         if (kk + 1 < KS) interleave_hint();
       }
       advance();
