@@ -1,10 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the decoder-stage hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of synthetic input: zero the fp32 gradient buffer,
-M x mls_stage_forward, one mls_stage_backward over the M stashed micro-batches (the 7B-shaped stage:
-4 layers, 4 micro-batches of 4096 tokens).  Prints ONE JSON line.  Inputs are resident in HBM before the
-timed region starts.  Model FLOPs: 3 x (dense GEMMs + causal-halved attention), recompute not credited.
+A step is one pass of the whole path over one batch of synthetic input: M x mls_stage_forward, then one
+mls_stage_backward over the M stashed micro-batches in overwrite mode, which writes the fp32 gradients of the step
+(nothing is zeroed beforehand and the gradient buffer is never read).  Default: the 7B-shaped stage, 4 layers, 4
+micro-batches of 4096 tokens.  Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
+Model FLOPs: 3 x (dense GEMMs + causal-halved attention), recompute not credited.  The timed process imports the
+library, the input generator and torch only; the CPU oracle is loaded by the cpu_baseline leg alone, after the
+timed region.
 """
 import argparse
 import json
@@ -60,25 +63,23 @@ def run_plan_sweep(plans, steps):
     import torch
     import synth
     import paper_2410_13333_amd as mls
-    from tests.helpers import to_device
     sh = synth.CONFIGS["sweep"]
     plans = plans or synth.plan_sweep()
     sh = sh.with_(layers=max(k for k, _ in plans), microbatches=max(m for _, m in plans))
     st = mls.Stage.from_shape(sh, seed=1004)           # one handle serves every plan
     shape = (sh.micro_batch, sh.seq, sh.hidden)
     mmax = max(m for _, m in plans)
-    xs = [to_device(synth.make_x(sh, 2004, mb)[0], sh.dtype) for mb in range(mmax)]
-    dy = torch.stack([to_device(synth.make_dy(sh, 3004, mb)[0], sh.dtype) for mb in range(mmax)])
+    xs = [synth.to_device(synth.make_x(sh, 2004, mb)[0], sh.dtype) for mb in range(mmax)]
+    dy = torch.stack([synth.to_device(synth.make_dy(sh, 3004, mb)[0], sh.dtype) for mb in range(mmax)])
     ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(mmax)]
     dx = torch.empty_like(dy)
     grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
     times = []
     for k, m in plans:
-        def step():
-            grads.zero_()
+        def step():     # the library's step form: the backward call writes the gradients, no zeroing pass
             for mb in range(m):
                 st.forward(xs[mb], k, ys[mb])
-            st.backward(dy[:m], grads, m, dx[:m])
+            st.backward(dy[:m], grads, m, dx[:m], overwrite=True)
         step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -277,15 +278,14 @@ def main():
     import torch
     import synth
     import paper_2410_13333_amd as mls
-    from tests.helpers import to_device
 
     sh = synth.CONFIGS[a.workload]
     K, M = sh.layers, sh.microbatches
     torch.cuda.set_device(0)
     st = mls.Stage.from_shape(sh, seed=1001, recompute=a.recompute)
     shape = (sh.micro_batch, sh.seq, sh.hidden)
-    xs = [to_device(synth.make_x(sh, 2001, mb)[0], sh.dtype) for mb in range(M)]
-    dy = torch.stack([to_device(synth.make_dy(sh, 3001, mb)[0], sh.dtype) for mb in range(M)])
+    xs = [synth.to_device(synth.make_x(sh, 2001, mb)[0], sh.dtype) for mb in range(M)]
+    dy = torch.stack([synth.to_device(synth.make_dy(sh, 3001, mb)[0], sh.dtype) for mb in range(M)])
     ys = [torch.empty(shape, dtype=st.tdtype, device="cuda") for _ in range(M)]
     dx = torch.empty_like(dy)
     grads = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
@@ -299,12 +299,19 @@ def main():
 
     for _ in range(a.warmup):
         step()
+    # the events mark the step boundaries on the stream the library launches on (torch's current stream, which the
+    # handle was created with); they are read after the timed region
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record()
+    for i in range(a.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
+    ms_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
 
     # per-kernel-class durations from HIP events on the stage's stream, over the same K-step region again
     st.timing(True)
@@ -334,6 +341,7 @@ def main():
                                f"{sh.n_q_heads}/{sh.n_kv_heads} heads x {sh.head_dim}, ffn {sh.ffn}, seq {sh.seq}, "
                                f"micro-batch {sh.micro_batch}" + (", activation recomputation" if a.recompute else ""),
                    "layers": K, "microbatches": M},
+        "ms_per_step_median": ms_median, "ms_per_step_min": per_step[0],
         "tokens_per_s": M * sh.tokens / (ms * 1e-3),
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "tau_ms_per_layer_microbatch": ms / (K * M),

@@ -305,3 +305,12 @@ def make_tokens(sh: EndsShape, seed, mb, skew=False):
 
 def make_targets(sh: EndsShape, seed, mb):
     return _token_draws(seed, TID_TARGETS, mb, sh.tokens, sh.vocab).reshape(sh.micro_batch, sh.seq)
+
+
+def to_device(storage, dtype):
+    """Storage array of this generator (uint16 bf16 bit patterns, or fp32) -> CUDA tensor of the storage type.
+    Plumbing only; torch is imported here so that the generator itself stays importable without it."""
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(storage.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(storage)).cuda()

@@ -12,12 +12,7 @@ def rel_err(got, ref):
     return float(np.linalg.norm(got - ref) / n) if n > 0 else float(np.linalg.norm(got))
 
 
-def to_device(storage, dtype):
-    """synth storage array (uint16 bf16 bits or fp32) -> CUDA tensor of the storage type."""
-    import torch
-    if dtype == "bf16":
-        return torch.from_numpy(storage.view(np.int16).copy()).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(storage)).cuda()
+to_device = synth.to_device      # synth storage array -> CUDA tensor of the storage type
 
 
 def to_host64(t):

@@ -169,17 +169,18 @@ def test_zero_layers_zero_microbatches_and_errors():
     assert e.value.code == -1
 
 
-@pytest.mark.parametrize("batched", [False, True])
+@pytest.mark.parametrize("batched", [0, 3, 17])
 @pytest.mark.parametrize("base", ["ragged", "fused"])
 def test_weight_gradient_contraction_given_identical_operands_1e4(base, batched):
     """The 1e-4 bar of the fp32-accumulated weight gradients: capture the bf16 operand pairs of every
     weight-gradient contraction of layer 0 and rebuild sum_mb X^T dY in fp64 from exactly those operands.
-    batched: all micro-batches go through ONE backward call (one contraction per weight over all of them, in a
-    two-layer stage); otherwise one call per micro-batch accumulates into the same gradient vector."""
+    batched = n > 0: n micro-batches go through ONE backward call (one contraction per weight over all of them, in a
+    two-layer stage; 17 is one more than a launch's 16 segments, so every weight takes a second, accumulating launch);
+    batched = 0: three micro-batches, one call per micro-batch accumulates into the same gradient vector."""
     import torch
     import paper_2410_13333_amd as mls
     sh = (RAGGED if base == "ragged" else FUSED_RAGGED).with_(layers=2 if batched else 1)
-    n, K = 3, sh.layers
+    n, K = batched or 3, sh.layers
     st = mls.Stage.from_shape(sh, seed=1000, max_inflight=n if batched else 1)
     g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
     ref = {k: 0.0 for k in ("w_d", "w_gu", "w_o", "w_qkv")}
