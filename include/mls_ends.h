@@ -64,6 +64,15 @@ int mls_embed_backward(mls_ends* e, const void* dX, float* grads, int32_t n);
  * and that gradient for the backward (FIFO; MLS_E_STASH when max_inflight are held). */
 int mls_head_forward(mls_ends* e, const void* y, const int32_t* targets, float loss_weight, float* loss);
 
+/* For callers that cannot allocate device memory or do not want the library to (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): mls_head_forward with the per-token loss terms, the one
+ * scratch buffer of its kernels, kept in a fixed array inside the library's code object (256 KiB per GPU, held until
+ * the process ends) instead of the handle's allocation.  Same arguments, same results bit for bit.  At most 65536
+ * tokens per micro-batch (seq * micro_batch), else MLS_E_RANGE.  Calls no hipMalloc / hipFree.  All calls on one GPU
+ * share that array, whatever their handle or stream: calls that overlap in time on one GPU race on it; calls that
+ * follow each other on one stream do not (every term a call reads it has written before). */
+int mls_head_forward_static(mls_ends* e, const void* y, const int32_t* targets, float loss_weight, float* loss);
+
 /* Backward of the n oldest kept head micro-batches, in push order: dY[i] = gradient w.r.t. y of micro-batch i
  * ([n, b, S, hidden], the dY that mls_stage_backward takes); grads_w_lm += sum_i nrm_i^T dlogits_i (one
  * contraction over all n, fp32); grads_gamma_f +=. */

@@ -86,6 +86,7 @@ def lib():
         L.mls_embed_forward.argtypes = [vp, vp, vp]
         L.mls_embed_backward.argtypes = [vp, vp, vp, i32]
         L.mls_head_forward.argtypes = [vp, vp, vp, C.c_float, vp]
+        L.mls_head_forward_static.argtypes = [vp, vp, vp, C.c_float, vp]
         L.mls_head_backward.argtypes = [vp, vp, i32, vp]
         L.mls_ends_grad_elems.argtypes = [vp]
         L.mls_ends_grad_elems.restype = sz
@@ -290,6 +291,9 @@ class Ends:
 
     def head_forward(self, y, targets, loss_weight, loss):
         _check(lib().mls_head_forward(self._h, _ptr(y), _ptr(targets), loss_weight, _ptr(loss)))
+
+    def head_forward_static(self, y, targets, loss_weight, loss):
+        _check(lib().mls_head_forward_static(self._h, _ptr(y), _ptr(targets), loss_weight, _ptr(loss)))
 
     def head_backward(self, grads, n, dy):
         _check(lib().mls_head_backward(self._h, _ptr(grads), n, _ptr(dy)))

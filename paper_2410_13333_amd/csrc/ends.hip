@@ -3,6 +3,7 @@
 // contractions and the RMSNorm are the kernels of the decoder stage; the kernels here are the HBM-bound rest.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -177,6 +178,34 @@ int64_t padded(int64_t n) { return n % 256 == 0 ? n + 64 : n; }
 
 }  // namespace
 
+// ---- Scratch of mls_head_forward_static: the per-token loss terms between the cross-entropy kernel and the mean.
+// One array per GPU (every device that loads this code object holds its own copy until the process ends).  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device address is looked up once per device,
+// with that device current, and kernels get that address as an argument.
+constexpr int STATIC_TOKENS = 65536;  // 256 KiB
+static __device__ __align__(256) float scratch[STATIC_TOKENS];
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[MAX_DEVICES] = {};
+// device address of `scratch` on the current device (looked up on first use there)
+hipError_t scratch_address(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    if ((e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
 struct mls_ends {
   mls_ends_config c;
   int dt, es, T;
@@ -295,6 +324,11 @@ int mls_ends_init(const mls_ends_config* cfg, uint64_t seed, void* hip_stream, m
     release(s);
     return fail_hip(e, "hipStreamSynchronize");
   }
+  float* sp = nullptr;  // set-up of mls_head_forward_static on this device
+  if ((e = scratch_address(&sp)) != hipSuccess) {
+    release(s);
+    return fail_hip(e, "hipGetSymbolAddress(scratch)");
+  }
   *out = s;
   return MLS_OK;
 }
@@ -354,9 +388,8 @@ int mls_embed_backward(mls_ends* s, const void* dX, float* grads, int32_t n) {
   return MLS_OK;
 }
 
-int mls_head_forward(mls_ends* s, const void* y, const int32_t* targets, float loss_weight, float* loss) {
-  if (!s || !y || !targets || !loss) return fail(MLS_E_NULL, "mls_head_forward: null argument");
-  if (uintptr_t(y) & 15) return fail(MLS_E_CONFIG, "mls_head_forward: y must be 16-byte aligned");
+// row_loss: T floats of scratch for the per-token loss terms (every one is written before the mean reads it)
+static int head_forward(mls_ends* s, const void* y, const int32_t* targets, float loss_weight, float* loss, float* row_loss) {
   if (s->h_count >= s->c.max_inflight) return fail(MLS_E_STASH, "head stash full: max_inflight micro-batches already forwarded");
   const int slot = (s->h_head + s->h_count) % s->c.max_inflight;
   const int T = s->T, h = s->c.hidden, V = s->c.vocab;
@@ -369,14 +402,30 @@ int mls_head_forward(mls_ends* s, const void* y, const int32_t* targets, float l
   HIP_TRY(gemm(s, mls::GEMM_NN, nr, s->wlm, dl, T, V, h, s->ld_h, s->ld_v, s->ld_v));
   const float scale = loss_weight / (float)T;
   if (s->dt == mls::DT_BF16)
-    hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(T), dim3(TH), 0, s->st, (bf16_t*)dl, s->ld_v, targets, V, scale, s->row_loss);
+    hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(T), dim3(TH), 0, s->st, (bf16_t*)dl, s->ld_v, targets, V, scale, row_loss);
   else
-    hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(TH), 0, s->st, (float*)dl, s->ld_v, targets, V, scale, s->row_loss);
+    hipLaunchKernelGGL(ce_kernel<float>, dim3(T), dim3(TH), 0, s->st, (float*)dl, s->ld_v, targets, V, scale, row_loss);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, s->st, s->row_loss, T, loss);
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, s->st, row_loss, T, loss);
   HIP_TRY(hipGetLastError());
   s->h_count++;
   return MLS_OK;
+}
+
+int mls_head_forward(mls_ends* s, const void* y, const int32_t* targets, float loss_weight, float* loss) {
+  if (!s || !y || !targets || !loss) return fail(MLS_E_NULL, "mls_head_forward: null argument");
+  if (uintptr_t(y) & 15) return fail(MLS_E_CONFIG, "mls_head_forward: y must be 16-byte aligned");
+  return head_forward(s, y, targets, loss_weight, loss, s->row_loss);
+}
+
+int mls_head_forward_static(mls_ends* s, const void* y, const int32_t* targets, float loss_weight, float* loss) {
+  if (!s || !y || !targets || !loss) return fail(MLS_E_NULL, "mls_head_forward_static: null argument");
+  if (uintptr_t(y) & 15) return fail(MLS_E_CONFIG, "mls_head_forward_static: y must be 16-byte aligned");
+  if (s->T > STATIC_TOKENS)
+    return fail(MLS_E_RANGE, "mls_head_forward_static: more than 65536 tokens per micro-batch (the static scratch holds 65536 loss terms)");
+  float* sp = nullptr;
+  if (hipError_t e = scratch_address(&sp)) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+  return head_forward(s, y, targets, loss_weight, loss, sp);
 }
 
 int mls_head_backward(mls_ends* s, float* grads, int32_t n, void* dY) {
