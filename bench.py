@@ -251,13 +251,71 @@ def run_model(steps, warmup, n_mb=4):
     return out
 
 
+def run_gemm(steps, warmup, data):
+    """The twelve contractions of one 7B layer x micro-batch through the stand-alone entry point mls_gemm (weight
+    gradients over the 4 micro-batches of the headline step), on operands of a chosen value distribution: the rate of
+    the same kernel depends on how many bits its operands toggle (the chip's power limit sets the shader clock)."""
+    import torch
+    import paper_2410_13333_amd as mls
+    T = 4096
+    shapes = {0: [(T, 12288, 4096), (T, 4096, 4096), (T, 22016, 4096), (T, 4096, 11008)],
+              1: [(T, 11008, 4096), (T, 4096, 22016), (T, 4096, 4096), (T, 4096, 12288)],
+              2: [(11008, 4096, 4 * T), (4096, 22016, 4 * T), (4096, 4096, 4 * T), (4096, 12288, 4 * T)]}
+    names = {0: "forward (NN)", 1: "data gradient (NT)", 2: "weight gradient (TN)"}
+    g = torch.Generator(device="cuda").manual_seed(5)
+
+    def operand(r, c):  # row-padded like the library's internal layout
+        ld = c + 64 if c % 256 == 0 else c
+        if data == "randn":
+            t = torch.randn(r, ld, device="cuda", generator=g)
+        elif data == "zeros":
+            t = torch.zeros(r, ld, device="cuda")
+        elif data == "ones":
+            t = torch.ones(r, ld, device="cuda")
+        elif data == "bits":
+            t = (torch.rand(r, ld, device="cuda", generator=g) < 0.5).float()
+        else:
+            raise SystemExit("--data must be randn, zeros, ones or bits")
+        return t.to(torch.bfloat16)[:, :c]
+    per_mode, tot_ms, tot_fl = {}, 0.0, 0.0
+    for mode in (0, 1, 2):
+        ms_mode = fl_mode = 0.0
+        for (M, N, K) in shapes[mode]:
+            a = operand(M, K) if mode != 2 else operand(K, M)
+            b = operand(K, N) if mode != 1 else operand(N, K)
+            c = torch.zeros(M, N + 64, device="cuda", dtype=torch.float32 if mode == 2 else torch.bfloat16)[:, :N]
+            for _ in range(warmup):
+                mls.gemm(mode, a, b, c)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                mls.gemm(mode, a, b, c)
+            e1.record()
+            torch.cuda.synchronize()
+            ms_mode += e0.elapsed_time(e1) / steps
+            fl_mode += 2.0 * M * N * K
+        per_mode[names[mode]] = {"ms": ms_mode, "tflops": fl_mode / (ms_mode * 1e-3) / 1e12}
+        tot_ms += ms_mode
+        tot_fl += fl_mode
+    tf = tot_fl / (tot_ms * 1e-3) / 1e12
+    return {"metric": "bf16 GEMM TFLOP/s (stand-alone)", "value": tf, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": tot_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": f"synthetic ({data})",
+            "config": {"workload": "the 12 contractions of one 7B layer x micro-batch, 4096 tokens, stand-alone launches"},
+            "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
+            "per_mode": per_mode}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step), model (embedding + stage + head + update)")
+    ap.add_argument("--workload", default="7b", help="7b (headline), 13b, 70b_tp4, tiny, sweep (16-plan linearity check), ends (first/last-stage layers), optim (AdamW step), model (embedding + stage + head + update), gemm (the layer's contractions stand-alone, --data)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--data", default="randn", help="gemm workload only: operand values, randn | zeros | ones | bits")
     ap.add_argument("--recompute", action="store_true", help="activation recomputation: keep only the layer inputs")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -270,6 +328,9 @@ def main():
         return
     if a.workload == "model":
         print(json.dumps(run_model(a.steps, a.warmup)))
+        return
+    if a.workload == "gemm":
+        print(json.dumps(run_gemm(a.steps, a.warmup, a.data)))
         return
     if a.workload == "optim":
         print(json.dumps(run_optim(a.steps, a.warmup)))

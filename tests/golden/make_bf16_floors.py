@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--mb", type=int, default=0, help="index of the micro-batch whose x and dY are used")
     ap.add_argument("--sets", default="operands,library,all")
     ap.add_argument("--redo", action="store_true")
+    ap.add_argument("--out", default=PATH, help="file to append to (default: the golden file beside this script)")
     a = ap.parse_args()
     base = synth.CONFIGS[a.config]
     K = a.layers or base.layers
@@ -78,14 +79,15 @@ def main():
             sets.append((s, O.ROUNDING_POINTS))
         else:
             sets.append((s, tuple(s.split("+"))))      # e.g. h+y
-    have = read()
+    out_path = a.out
+    have = read(out_path)
     if not a.redo:
         sets = [(n, m) for n, m in sets if (a.config, K, a.mb, n) not in have]
     if not sets:
         print("nothing to do")
         return
-    if not os.path.exists(PATH):
-        with open(PATH, "w") as f:
+    if not os.path.exists(out_path):
+        with open(out_path, "w") as f:
             f.write("# bf16 roundings alone: relative Frobenius distance from the exact fp64 oracle (oracle only, CPU);\n"
                     "# written by tests/golden/make_bf16_floors.py; seeds weights/x/dY = %d/%d/%d\n"
                     "# config\tlayers\tmicro-batch\trounded set\ty\tdX\tworst gradient\twhich\n" % SEEDS)
@@ -101,24 +103,35 @@ def main():
         (wl, wn), _ = max(errs.items(), key=lambda kv: kv[1])
         line = "%s\t%d\t%d\t%s\t%.3e\t%.3e\t%.3e\t%s" % (a.config, K, a.mb, name, rel_err(y, ey), rel_err(dx, edx),
                                                         worst, f"{wn}[{wl}]")
-        with open(PATH, "a") as f:
+        with open(out_path, "a") as f:
             f.write(line + "\n")
         print(line, f"({time.time() - t0:.0f} s)", flush=True)
 
 
 def _run(sh, p64, xseed, dyseed, K, mb, hook):
-    """One micro-batch (index mb of the seeded stream) through K layers and back."""
+    """One micro-batch (index mb of the seeded stream) through K layers and back.  To bound the memory (a layer's
+    cache holds its S x S probabilities: 4 to 5 GB at these shapes) only the layer inputs are kept on the way up and
+    each layer's forward is run again on the way down; the hook is a pure function, so this changes no value."""
     W = [synth.split_params(sh, p64, l) for l in range(K)]
     _, x = synth.make_x(sh, xseed, mb)
     _, dy = synth.make_dy(sh, dyseed, mb)
-    y, caches = O.stage_forward(x, W, sh, K, hook)
-    dx, grads = O.stage_backward(dy, W, caches, sh, hook)
-    per = synth.layer_param_elems(sh)
-    flat = np.zeros(K * per)
+    xs = [np.array(x, dtype=np.float64)]
     for l in range(K):
+        y, _ = O.layer_forward(xs[l], W[l], sh, hook)
+        xs.append(y)
+        print(f"  forward layer {l} done", flush=True)
+    per = synth.layer_param_elems(sh)
+    flat = np.zeros(K * per, dtype=np.float32)     # distances of 1e-3 and more: fp32 storage of the result is ample
+    d = np.array(dy, dtype=np.float64)
+    for l in range(K - 1, -1, -1):
+        _, cache = O.layer_forward(xs[l], W[l], sh, hook)
+        d, g = O.layer_backward(d, W[l], cache, sh, hook)
+        del cache
         for name, tid, r, c, off in synth.param_layout(sh):
-            flat[l * per + off: l * per + off + r * c] = grads[l][name].reshape(-1)
-    return y, dx, flat
+            flat[l * per + off: l * per + off + r * c] = g[name].reshape(-1)
+        del g
+        print(f"  backward layer {l} done", flush=True)
+    return xs[K], d, flat
 
 
 if __name__ == "__main__":
