@@ -401,7 +401,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
   // access patterns spread over all banks.  `col0` is the column of the whole problem at which this launch's
   // column 0 sits (a launch may cover a column range).
   __syncthreads();  // every wave has read its last fragments and every DMA has landed
-  unsigned char* ws = smem + wave * (64 * 1024 / NW);
+  // (the rotary epilogue packs the staging areas, 4 KiB each, to make room for its exchange buffers)
+  unsigned char* ws = smem + wave * (EPI == EPI_ROPE ? 4096 : 64 * 1024 / NW);
   constexpr int CW = BN / WN;                         // columns of a wave tile
   constexpr int RB = CW * 2, NCH = RB / 16;           // bytes and 16-byte chunks per staged row (bf16)
   constexpr int RPI = 64 / NCH, NT = 32 / RPI;        // rows per whole-wave access, accesses per 32 rows
@@ -448,12 +449,26 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
         // Rotation on the fp32 accumulators.  A head of 64 columns is this wave's two 32-column tiles: the partner of
         // a value sits in the same lane, in the other tile.  A head of 128 columns spans this wave's 64 columns and
         // those of the wave next to it along N (wave ^ 2): the waves exchange their fp32 rows through LDS behind the
-        // bf16 staging areas (8 KiB per wave, 16-byte chunks XOR-swizzled by row).
+        // bf16 staging areas (two buffers of 8 KiB per wave, alternating with the 32-row block so that one workgroup
+        // barrier per block suffices; 16-byte chunks XOR-swizzled by row).  The table entries are requested before
+        // the exchange so that their latency passes behind the barrier.
         const bool wide = rope.head_dim == 128;
         const bool rot = col0 + n0 + wn < rope.rot_cols;  // whole heads: uniform over the wave
         const int d2 = rope.head_dim >> 1;
-        unsigned char* fx = smem + 64 * 1024;
+        unsigned char* fx = smem + 32 * 1024 + (i & 1) * NW * 8192;
         auto fx_at = [&](int w, int chunk) { return fx + w * 8192 + r32 * 256 + ((chunk ^ (r32 & 15)) << 4); };
+        float4 cs[TN][4], sn[TN][4];
+        if (rot) {
+          const int row = row0 + r32;
+          const int64_t at = int64_t((row < M ? row : 0) % rope.seq) * d2 + hi * 4;
+#pragma unroll
+          for (int j = 0; j < (wide ? TN : 1); j++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+              cs[j][g] = *reinterpret_cast<const float4*>(rope.cos_tab + at + j * 32 + 8 * g);
+              sn[j][g] = *reinterpret_cast<const float4*>(rope.sin_tab + at + j * 32 + 8 * g);
+            }
+        }
         if (wide) {
           if (rot) {
 #pragma unroll
@@ -466,8 +481,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
           __syncthreads();
         }
         if (rot) {
-          const int row = row0 + r32;
-          const int64_t at = int64_t((row < M ? row : 0) % rope.seq) * d2 + hi * 4;
           const bool first = !((wave >> 1) & 1);  // wide: this wave holds the first halves of its pairs
 #pragma unroll
           for (int g = 0; g < 4; g++) {
@@ -475,9 +488,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
 #pragma unroll
               for (int j = 0; j < TN; j++) {
                 const float4 pv = *reinterpret_cast<const float4*>(fx_at(wave ^ 2, j * 8 + 2 * g + hi));
-                const float4 cs = *reinterpret_cast<const float4*>(rope.cos_tab + at + j * 32 + 8 * g);
-                const float4 sn = *reinterpret_cast<const float4*>(rope.sin_tab + at + j * 32 + 8 * g);
-                const float pp[4] = {pv.x, pv.y, pv.z, pv.w}, c[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+                const float pp[4] = {pv.x, pv.y, pv.z, pv.w};
+                const float c[4] = {cs[j][g].x, cs[j][g].y, cs[j][g].z, cs[j][g].w};
+                const float sv[4] = {sn[j][g].x, sn[j][g].y, sn[j][g].z, sn[j][g].w};
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                   const float own = acc[i][j][g * 4 + e];
@@ -486,9 +499,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
                 }
               }
             } else {
-              const float4 cs = *reinterpret_cast<const float4*>(rope.cos_tab + at + 8 * g);
-              const float4 sn = *reinterpret_cast<const float4*>(rope.sin_tab + at + 8 * g);
-              const float c[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+              const float c[4] = {cs[0][g].x, cs[0][g].y, cs[0][g].z, cs[0][g].w};
+              const float sv[4] = {sn[0][g].x, sn[0][g].y, sn[0][g].z, sn[0][g].w};
 #pragma unroll
               for (int e = 0; e < 4; e++) {
                 const float u1 = acc[i][0][g * 4 + e], u2 = acc[i][1][g * 4 + e];
@@ -498,7 +510,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_dma_kernel(const bf16_t* __restr
             }
           }
         }
-        if (wide) __syncthreads();  // the partner has read this wave's rows: the next 32 rows may overwrite them
       }
       // combine in the accumulator layout, in place
       constexpr int ZRB = CW, ZNCH = ZRB / 16, ZRPL = ZRB < 256 ? 256 / ZRB : 1;  // SwiGLU product: half as many columns, staged behind the 8 KiB
@@ -566,10 +577,12 @@ hipError_t launch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, in
                   const RopeArgs* rope = nullptr) {
   // (the forward form keeps its A tiles in a ring of 5 stages beside the NS stages of B: see PAIRA in the kernel)
   constexpr bool PAIRA = !ATR && BTR && BK == 32 && PIPE == PIPE_SKEW && !SEG && NS == 4;
-  constexpr int LDS = PAIRA ? (5 * BM + NS * BN) * BK * 2 : NS * (BM + BN) * BK * 2;
-  // the rotary epilogue keeps 8 KiB of fp32 rows per wavefront behind the 64 KiB of bf16 staging areas and pairs the
-  // two 32-column tiles of a wavefront
-  static_assert(EPI != EPI_ROPE || (LDS >= (64 + 8 * NW) * 1024 && BN / (NW / 2) == 64), "rotary epilogue: LDS or wave tile");
+  constexpr int LDS_PIPE = PAIRA ? (5 * BM + NS * BN) * BK * 2 : NS * (BM + BN) * BK * 2;
+  // the rotary epilogue keeps two buffers of 8 KiB of fp32 rows per wavefront behind 32 KiB of bf16 staging areas and
+  // pairs the two 32-column tiles of a wavefront
+  static_assert(EPI != EPI_ROPE || BN / (NW / 2) == 64, "rotary epilogue: wave tile");
+  constexpr int LDS_ROPE = (32 + 16 * NW) * 1024;
+  constexpr int LDS = EPI == EPI_ROPE && LDS_ROPE > LDS_PIPE ? LDS_ROPE : LDS_PIPE;
   auto kern = gemm_dma_kernel<BM, BN, BK, NS, ATR, BTR, EPI, PIPE, SEG, NW>;
   SegArgs sa = {};
   if (segs) sa = *segs;
