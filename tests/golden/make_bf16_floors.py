@@ -11,6 +11,9 @@ parameter gradient from the exact run.  Sets:
                                 has to round these whatever else it does
     "library"                   the tensors the HIP library keeps in bf16 (LIBRARY_BF16 below, maintained by hand
                                 from the library's data layout)
+    "library_fp32_stream"       the same without the residual stream (h, y forward; dh, dx backward), i.e. what keeping
+                                that stream in fp32 would leave.  (dh is also an operand of two products; rounding
+                                only that use is not expressible with the hook, so this set is a lower bound.)
     "all"                       every named tensor
 
 The paper prints no numeric value for this computation (it names the architecture only, Sec. 7.1), so these are
@@ -77,6 +80,8 @@ def main():
             sets.append((s, LIBRARY_BF16))
         elif s == "all":
             sets.append((s, O.ROUNDING_POINTS))
+        elif s == "library_fp32_stream":      # what an fp32 residual stream (forward h, y; backward dh, dx) would leave
+            sets.append((s, tuple(n for n in LIBRARY_BF16 if n not in ("h", "y", "dh", "dx"))))
         else:
             sets.append((s, tuple(s.split("+"))))      # e.g. h+y
     out_path = a.out
