@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmls.so")
-SOURCES = ["stage.hip", "gemm_bf16.hip", "gemm_bf16_dma.hip", "gemm_f32.hip", "attention_bf16.hip", "attention_f32.hip", "elementwise.hip", "plan.cpp", "ends.hip", "optim.hip"]
+SOURCES = ["stage.hip", "gemm_bf16.hip", "gemm_bf16_dma.hip", "gemm_bf16_m16.hip", "gemm_f32.hip", "attention_bf16.hip", "attention_f32.hip", "elementwise.hip", "plan.cpp", "ends.hip", "optim.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

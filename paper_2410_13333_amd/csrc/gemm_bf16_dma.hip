@@ -18,6 +18,7 @@
 // accumulators in AGPRs) or 8 (two per SIMD, 128x64 each, under 256 registers, so that one wavefront issues MFMAs
 // while the other waits at the barrier or for its fragments).  bf16 epilogues leave through an LDS staging pass
 // that turns the accumulator layout into whole-row 16-byte accesses.
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -644,6 +645,17 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
   // -3 %), the fp32 read-modify-write mode runs 4 (128x128 each; 8 measured 2.5 % slower there).
   constexpr int NW = EPI != EPI_F32_ACC ? 8 : 4;
   const ColumnPlan cp = plan_columns(M, N);
+  // MLS_OLD_GEMM in the environment keeps the 32x32x16 kernels of this file for every tile (for comparisons)
+  static const bool use_m16 = getenv("MLS_OLD_GEMM") == nullptr;
+  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(K) && (EPI == EPI_SWIGLU || EPI == EPI_ROPE || (x.xf == 0 && x.ldx == 0))) {
+    const int mode = ATR ? mls::GEMM_TN : BTR ? mls::GEMM_NN : mls::GEMM_NT;
+    hipError_t e;
+    if (EPI == EPI_SWIGLU) e = mls::gemm_m16_swiglu(A, B, C, x.X, M, cp.n1, K, lda, ldb, ldc, x.ldx, ab, bb, st);
+    else if (EPI == EPI_ROPE) e = mls::gemm_m16_rope(A, B, C, M, cp.n1, K, lda, ldb, ldc, ab, bb, x.rope->cos_tab, x.rope->sin_tab,
+                                                     x.rope->seq, x.rope->rot_cols, x.rope->head_dim, st);
+    else e = mls::gemm_m16(mode, A, B, C, R, M, cp.n1, K, lda, ldb, ldc, ldr, ab, bb, st);
+    if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
+  } else
   if (cp.n1 > 0) {
     hipError_t e = launch<256, 256, BK, NS, ATR, BTR, EPI, PIPE, false, NW>(A, B, C, R, M, cp.n1, K, lda, ldb, ldc, ldr, ab, bb, st,
                                                                            nullptr, 0, x.X, x.ldx, x.xf, x.rope);
@@ -706,6 +718,11 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   const uint32_t ab = uint32_t(int64_t(kseg) * lda * 2), bb = uint32_t(int64_t(kseg) * ldb * 2);
   const ColumnPlan cp = plan_columns(M, N);
   const int ovw = overwrite ? 1 : 0;
+  static const bool use_m16 = getenv("MLS_OLD_GEMM") == nullptr;
+  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(kseg)) {
+    hipError_t e = mls::gemm_m16_tn_segments(A, B, nseg, C, M, cp.n1, kseg, lda, ldb, ldc, ab, bb, st, gu_f, overwrite);
+    if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
+  } else
   if (cp.n1 > 0) {
     hipError_t e = launch<256, 256, 32, 4, true, true, EPI_F32_ACC, PIPE_SKEW, true>(sa.a[0], sa.b[0], C, nullptr, M, cp.n1, kseg, lda,
                                                                                     ldb, ldc, 0, ab, bb, st, &sa, 0, nullptr, ovw, gu_f);

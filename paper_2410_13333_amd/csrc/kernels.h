@@ -44,6 +44,18 @@ bool gemm_tn_segments_ok(int kseg, int64_t lda, int64_t ldb);
 hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
                                  int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f = 0,
                                  bool overwrite = false);
+// the 256x256 tiles of a problem on the 16x16x32 form of the matrix instruction (gemm_bf16_m16.hip); K % 32 == 0
+bool gemm_m16_ok(int K);
+hipError_t gemm_m16(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
+                    int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st);
+hipError_t gemm_m16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int N, int K, int64_t lda, int64_t ldw,
+                           int64_t ldgu, int64_t ldz, uint32_t ab, uint32_t bb, hipStream_t st);
+hipError_t gemm_m16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
+                         uint32_t ab, uint32_t bb, const float* cos_tab, const float* sin_tab, int seq, int rot_cols,
+                         int head_dim, hipStream_t st);
+hipError_t gemm_m16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
+                                int64_t lda, int64_t ldb, int64_t ldc, uint32_t ab, uint32_t bb, hipStream_t st, int gu_f,
+                                bool overwrite);
 hipError_t fill_zero_f32(float* p, size_t n, hipStream_t st);
 // SwiGLU fused into the gate/up contraction (bf16, f % 32 == 0, DMA path).  Interleaved gate/up column order:
 // 32 gate columns, the 32 up columns of the same indices, and so on (gu_interleaved_col in common.h).
