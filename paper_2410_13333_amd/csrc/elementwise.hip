@@ -351,6 +351,26 @@ __global__ __launch_bounds__(EW_THREADS) void gu_permute_kernel(const bf16_t* __
   *reinterpret_cast<uint4*>(dst + t * ld_dst + (to_interleaved ? ci : c)) = v;
 }
 
+// dst[c][r] = src[r][c] for a rows x cols bf16 matrix (rows, cols multiples of 8): 64 x 64 tiles through LDS, padded
+// against bank conflicts; 256 threads, each moves 16 elements
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
+                                                             bf16_t* __restrict__ dst, int64_t ld_dst, int rows, int cols) {
+  __shared__ bf16_t tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    const int r = ty + i * 4;
+    if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = src[int64_t(r0 + r) * ld_src + c0 + tx];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    const int c = ty + i * 4;
+    if (c0 + c < cols && r0 + tx < rows) dst[int64_t(c0 + c) * ld_dst + r0 + tx] = tile[tx][c];
+  }
+}
+
 inline int blocks_for(int64_t n) { return int((n + EW_THREADS - 1) / EW_THREADS); }
 
 }  // namespace
@@ -452,6 +472,13 @@ hipError_t gu_permute(const void* src, int64_t ld_src, void* dst, int64_t ld_dst
   if (total == 0) return hipSuccess;
   hipLaunchKernelGGL(gu_permute_kernel, dim3(blocks_for(total)), dim3(EW_THREADS), 0, st, (const bf16_t*)src, ld_src,
                      (bf16_t*)dst, ld_dst, total, f, to_interleaved);
+  return hipGetLastError();
+}
+
+hipError_t transpose_bf16(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int rows, int cols, hipStream_t st) {
+  if (rows == 0 || cols == 0) return hipSuccess;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, st, (const bf16_t*)src,
+                     ld_src, (bf16_t*)dst, ld_dst, rows, cols);
   return hipGetLastError();
 }
 

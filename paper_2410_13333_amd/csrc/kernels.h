@@ -97,6 +97,8 @@ hipError_t swiglu_bwd(int dt, const void* dz, int64_t ld_dz, const void* gu, int
 // offset + scale*z(seed, tensor, layer, r*cols + c), rounded once
 hipError_t fill_normal(int dt, void* out, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, uint32_t tensor,
                        uint32_t layer, double scale, double offset, hipStream_t st, int gu_f = 0);
+// dst[c][r] = src[r][c], bf16, rows x cols (used for the transposed weight copies of the data-gradient contractions)
+hipError_t transpose_bf16(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int rows, int cols, hipStream_t st);
 // gu_f > 0 above: a [rows, 2 gu_f] gate/up tensor is written in the interleaved column order.  gu_permute moves a
 // bf16 [rows, 2f] matrix between the public and the interleaved column order.
 hipError_t gu_permute(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int f,

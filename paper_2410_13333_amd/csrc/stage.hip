@@ -94,6 +94,11 @@ struct mls_stage {
   size_t ilayer_params;  // elements per layer, internal (row-padded) layout
   size_t ioff_g1, ioff_wqkv, ioff_wo, ioff_g2, ioff_wgu, ioff_wd;
   char* params = nullptr;  // storage type, internal layout
+  // Transposed copies of the four weight matrices of every layer (bf16 storage only): the data-gradient contractions
+  // dX = dY W^T then read W^T as a [k][n] operand, whose tiles come in whole 512-byte rows, instead of W as a second
+  // [row][k] operand, whose 32-deep tiles are half cache lines.  Refreshed whenever the weights change.
+  char* params_t = nullptr;
+  size_t tlayer_params = 0, toff_wqkv = 0, toff_wo = 0, toff_wgu = 0, toff_wd = 0;  // elements per layer, offsets
   float *cos_tab = nullptr, *sin_tab = nullptr;
   LayerStash ls;
   // Stash entry of one (micro-batch, layer): the full LayerStash, or with activation recomputation only the
@@ -118,6 +123,7 @@ struct mls_stage {
     return stash + (size_t(slot) * c.max_layers + layer) * entry_bytes;
   }
   char* param(int layer, size_t ioff) const { return params + (size_t(layer) * ilayer_params + ioff) * es; }
+  char* param_t(int layer, size_t toff) const { return params_t + (size_t(layer) * tlayer_params + toff) * es; }
 };
 
 namespace {
@@ -185,6 +191,19 @@ int init_weights(mls_stage* s, uint64_t seed) {
   return MLS_OK;
 }
 
+// the transposed weight copies of every layer from the current weights (bf16 storage)
+int refresh_transposed(mls_stage* s) {
+  if (!s->params_t) return MLS_OK;
+  const mls_config& c = s->c;
+  for (int l = 0; l < c.max_layers; l++) {
+    HIP_TRY(mls::transpose_bf16(s->param(l, s->ioff_wqkv), s->ld_qkv, s->param_t(l, s->toff_wqkv), s->ld_h, c.hidden, s->qkvw, s->st));
+    HIP_TRY(mls::transpose_bf16(s->param(l, s->ioff_wo), s->ld_h, s->param_t(l, s->toff_wo), s->ld_qd, s->qd, c.hidden, s->st));
+    HIP_TRY(mls::transpose_bf16(s->param(l, s->ioff_wgu), s->ld_gu, s->param_t(l, s->toff_wgu), s->ld_h, c.hidden, 2 * c.ffn, s->st));
+    HIP_TRY(mls::transpose_bf16(s->param(l, s->ioff_wd), s->ld_h, s->param_t(l, s->toff_wd), s->ld_f, c.ffn, c.hidden, s->st));
+  }
+  return MLS_OK;
+}
+
 // dense <-> row-padded copies of a rows x cols matrix of the storage type
 hipError_t copy2d(const mls_stage* s, void* dst, int64_t ld_dst, const void* src, int64_t ld_src, int64_t rows,
                   int64_t cols) {
@@ -241,13 +260,18 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
   char* dh = s->dh + size_t(w) * s->mb_h;
   char* dqkv = s->dqkv + size_t(w) * s->mb_qkv;
   // MLP
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->ioff_wd), s->dz, nullptr, T, f, h, ld_dy, lh, lf));
+  // data gradients dX = dY W^T: with the transposed weight copies a plain product against W^T (bf16), else the NT form
+  const bool wt = s->params_t != nullptr;
+  if (wt) LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NN, dy, s->param_t(layer, s->toff_wd), s->dz, nullptr, T, f, h, ld_dy, lf, lf));
+  else LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dy, s->param(layer, s->ioff_wd), s->dz, nullptr, T, f, h, ld_dy, lh, lf));
   LAUNCH(CLS_SWIGLU, mls::swiglu_bwd(s->dt, s->dz, lf, e + L.gu, lg, dgu, lg, T, f, s->st, s->fuse_gu));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
+  if (wt) LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NN, dgu, s->param_t(layer, s->toff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lh, lh));
+  else LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dgu, s->param(layer, s->ioff_wgu), s->dbuf, nullptr, T, h, 2 * f, lg, lg, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, e + L.h, lh, s->param(layer, s->ioff_g2), (const float*)(e + L.r2),
                                     dy, ld_dy, dh, lh, g + s->off_g2, s->partial2, T, h, s->st, ow, !first, last));
   // attention
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
+  if (wt) LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NN, dh, s->param_t(layer, s->toff_wo), s->dc, nullptr, T, qd, h, lh, lo, lo));
+  else LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dh, s->param(layer, s->ioff_wo), s->dc, nullptr, T, qd, h, lh, lh, lo));
   // the bf16 attention-backward kernels turn dq and dk back by the rotary angle as they store them
   const bool unrot = s->dt == mls::DT_BF16;
   LAUNCH(CLS_ATTN_BWD, mls::attn_bwd(s->dt, e + L.qkv, lq, e + L.o, lo, (const float*)(e + L.lse), s->dc, lo, dqkv, lq,
@@ -256,7 +280,8 @@ int layer_backward_data(mls_stage* s, int layer, const char* x, const char* e, i
   if (!unrot)
     LAUNCH(CLS_ROPE, mls::rope_inplace(s->dt, dqkv, s->cos_tab, s->sin_tab, T, c.seq, c.n_q_heads + c.n_kv_heads,
                                        c.head_dim, lq, -1.f, s->st));
-  LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
+  if (wt) LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NN, dqkv, s->param_t(layer, s->toff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lh, lh));
+  else LAUNCH(CLS_GEMM_NT, gemm(s, mls::GEMM_NT, dqkv, s->param(layer, s->ioff_wqkv), s->dbuf, nullptr, T, h, wq, lq, lq, lh));
   LAUNCH(CLS_NORM, mls::rmsnorm_bwd(s->dt, s->dbuf, lh, x, lh, s->param(layer, s->ioff_g1), (const float*)(e + L.r1),
                                     dh, lh, dx, ld_dx, g + s->off_g1, s->partial, T, h, s->st, ow, !first, last));
   return MLS_OK;
@@ -306,6 +331,12 @@ void layout(mls_stage* s) {
   s->ioff_wgu = s->ioff_g2 + h;
   s->ioff_wd = s->ioff_wgu + h * s->ld_gu;
   s->ilayer_params = s->ioff_wd + f * s->ld_h;
+  // transposed copies: w_qkv^T [qkvw, ld_h], w_o^T [h, ld_qd], w_gu^T [2f, ld_h], w_d^T [h, ld_f]
+  s->toff_wqkv = 0;
+  s->toff_wo = s->toff_wqkv + size_t(s->qkvw) * s->ld_h;
+  s->toff_wgu = s->toff_wo + h * s->ld_qd;
+  s->toff_wd = s->toff_wgu + 2 * f * s->ld_h;
+  s->tlayer_params = s->toff_wd + h * s->ld_f;
   s->fuse_gu = s->dt == mls::DT_BF16 && mls::gemm_swiglu_ok(s->T, c.ffn, c.hidden, s->ld_h, s->ld_gu) &&
                mls::gemm_tn_segments_ok(s->T, s->ld_h, s->ld_gu);
 
@@ -343,6 +374,7 @@ std::vector<Alloc> allocations(mls_stage* s) {
   const int nb = mls::rmsnorm_bwd_blocks(s->T);
   return {
       {(void**)&s->params, size_t(c.max_layers) * s->ilayer_params * s->es, 0},
+      {(void**)&s->params_t, s->dt == mls::DT_BF16 ? size_t(c.max_layers) * s->tlayer_params * s->es : 0, 0},
       {(void**)&s->cos_tab, size_t(c.seq) * (c.head_dim / 2) * 4, 2},
       {(void**)&s->sin_tab, size_t(c.seq) * (c.head_dim / 2) * 4, 2},
       {(void**)&s->stash, nmb * c.max_layers * s->entry_bytes, 1},
@@ -363,7 +395,7 @@ std::vector<Alloc> allocations(mls_stage* s) {
 }
 
 void release(mls_stage* s) {
-  void* p[] = {s->params, s->cos_tab, s->sin_tab, s->stash, s->rc_scratch, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
+  void* p[] = {s->params, s->params_t, s->cos_tab, s->sin_tab, s->stash, s->rc_scratch, s->g0, s->g1, s->dz, s->dgu, s->dbuf, s->dh, s->dc, s->dqkv,
                s->delta, s->partial, s->partial2, s->gqa_part};
   for (void* q : p)
     if (q) (void)hipFree(q);
@@ -412,6 +444,10 @@ int mls_stage_init(const mls_config* cfg, uint64_t seed, void* hip_stream, mls_s
     }
   }
   if (int rc = init_weights(s, seed)) {
+    release(s);
+    return rc;
+  }
+  if (int rc = refresh_transposed(s)) {
     release(s);
     return rc;
   }
@@ -534,7 +570,7 @@ int mls_stage_memory(const mls_config* cfg, mls_memory* out) {
   mls_memory m = {};
   for (const Alloc& al : allocations(&tmp)) (al.kind == 0 ? m.param_bytes : al.kind == 1 ? m.stash_bytes : m.workspace_bytes) += al.bytes;
   m.total_bytes = m.param_bytes + m.stash_bytes + m.workspace_bytes;
-  m.param_bytes_per_layer = tmp.ilayer_params * tmp.es;
+  m.param_bytes_per_layer = (tmp.ilayer_params + (tmp.dt == mls::DT_BF16 ? tmp.tlayer_params : 0)) * tmp.es;
   m.stash_bytes_per_layer_microbatch = tmp.entry_bytes;
   m.grad_bytes_per_layer = tmp.layer_params * 4;
   *out = m;
@@ -597,6 +633,7 @@ int mls_stage_set_params(mls_stage* s, const void* src) {
       else
         HIP_TRY(copy2d(s, s->param(l, e.ioff), e.ld, p, e.cols, e.rows, e.cols));
     }
+  if (int rc = refresh_transposed(s)) return rc;
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
