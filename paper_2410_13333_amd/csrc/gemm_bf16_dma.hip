@@ -647,12 +647,12 @@ hipError_t dispatch(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
   const ColumnPlan cp = plan_columns(M, N);
   // MLS_OLD_GEMM in the environment keeps the 32x32x16 kernels of this file for every tile (for comparisons)
   static const bool use_m16 = getenv("MLS_OLD_GEMM") == nullptr;
-  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(K) && (EPI == EPI_SWIGLU || EPI == EPI_ROPE || (x.xf == 0 && x.ldx == 0))) {
+  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(ATR ? mls::GEMM_TN : mls::GEMM_NN, K) && (EPI == EPI_SWIGLU || EPI == EPI_ROPE || (x.xf == 0 && x.ldx == 0))) {
     const int mode = ATR ? mls::GEMM_TN : BTR ? mls::GEMM_NN : mls::GEMM_NT;
     hipError_t e;
-    if (EPI == EPI_SWIGLU) e = mls::gemm_m16_swiglu(A, B, C, x.X, M, cp.n1, K, lda, ldb, ldc, x.ldx, ab, bb, st);
+    if (EPI == EPI_SWIGLU) e = mls::gemm_m16_swiglu(A, B, C, x.X, M, cp.n1, K, lda, ldb, ldc, x.ldx, ab, bb, st, !BTR);
     else if (EPI == EPI_ROPE) e = mls::gemm_m16_rope(A, B, C, M, cp.n1, K, lda, ldb, ldc, ab, bb, x.rope->cos_tab, x.rope->sin_tab,
-                                                     x.rope->seq, x.rope->rot_cols, x.rope->head_dim, st);
+                                                     x.rope->seq, x.rope->rot_cols, x.rope->head_dim, st, !BTR);
     else e = mls::gemm_m16(mode, A, B, C, R, M, cp.n1, K, lda, ldb, ldc, ldr, ab, bb, st);
     if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
   } else
@@ -719,7 +719,7 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
   const ColumnPlan cp = plan_columns(M, N);
   const int ovw = overwrite ? 1 : 0;
   static const bool use_m16 = getenv("MLS_OLD_GEMM") == nullptr;
-  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(kseg)) {
+  if (cp.n1 > 0 && use_m16 && mls::gemm_m16_ok(mls::GEMM_TN, kseg)) {
     hipError_t e = mls::gemm_m16_tn_segments(A, B, nseg, C, M, cp.n1, kseg, lda, ldb, ldc, ab, bb, st, gu_f, overwrite);
     if (e != hipSuccess || cp.tail == TAIL_NONE) return e;
   } else
@@ -736,37 +736,42 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
                                                                              ldb, ldc, 0, ab, bb, st, &sa, cp.n1, nullptr, ovw, gu_f);
 }
 
-bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw) {
-  return f > 0 && f % 32 == 0 && gemm_bf16_dma_ok(GEMM_NN, M, 2 * f, K, lda, ldw);
+bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw, bool w_nk) {
+  return f > 0 && f % 32 == 0 && gemm_bf16_dma_ok(w_nk ? GEMM_NT : GEMM_NN, M, 2 * f, K, lda, ldw);
 }
 
 hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int f, int K, int64_t lda,
-                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st) {
+                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st, bool w_nk) {
   if (M == 0 || f == 0) return hipSuccess;
-  if (f % 32 || !gemm_bf16_dma_ok(GEMM_NN, M, 2 * f, K, lda, ldw)) return hipErrorInvalidValue;
+  if (!gemm_swiglu_ok(M, f, K, lda, ldw, w_nk)) return hipErrorInvalidValue;
   Extra x;
   x.X = Z;
   x.ldx = ldz;
-  return dispatch<false, true, EPI_SWIGLU>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), GU, nullptr, M,
-                                           2 * f, K, lda, ldw, ldgu, 0, uint32_t(int64_t(M) * lda * 2),
-                                           uint32_t(int64_t(K) * ldw * 2), st, x);
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  const uint32_t ab = uint32_t(int64_t(M) * lda * 2), wb = uint32_t(int64_t(w_nk ? 2 * f : K) * ldw * 2);
+  if (w_nk) return dispatch<false, false, EPI_SWIGLU>(a, w, GU, nullptr, M, 2 * f, K, lda, ldw, ldgu, 0, ab, wb, st, x);
+  return dispatch<false, true, EPI_SWIGLU>(a, w, GU, nullptr, M, 2 * f, K, lda, ldw, ldgu, 0, ab, wb, st, x);
 }
 
-bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim) {
+bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim, bool w_nk) {
   return (head_dim == 64 || head_dim == 128) && seq > 0 && rot_cols >= 0 && rot_cols <= N && rot_cols % head_dim == 0 &&
-         N % head_dim == 0 && gemm_bf16_dma_ok(GEMM_NN, M, N, K, lda, ldw);
+         N % head_dim == 0 && gemm_bf16_dma_ok(w_nk ? GEMM_NT : GEMM_NN, M, N, K, lda, ldw);
 }
 
 hipError_t gemm_bf16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
-                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st) {
+                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st,
+                          bool w_nk) {
   if (M == 0 || N == 0) return hipSuccess;
-  if (!cos_tab || !sin_tab || !gemm_rope_ok(M, N, K, lda, ldw, seq, rot_cols, head_dim)) return hipErrorInvalidValue;
+  if (!cos_tab || !sin_tab || !gemm_rope_ok(M, N, K, lda, ldw, seq, rot_cols, head_dim, w_nk)) return hipErrorInvalidValue;
   const RopeArgs ra = {cos_tab, sin_tab, seq, rot_cols, head_dim};
   Extra x;
   x.rope = &ra;
-  return dispatch<false, true, EPI_ROPE>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), C, nullptr, M, N, K,
-                                         lda, ldw, ldc, 0, uint32_t(int64_t(M) * lda * 2), uint32_t(int64_t(K) * ldw * 2),
-                                         st, x);
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  const uint32_t ab = uint32_t(int64_t(M) * lda * 2), wb = uint32_t(int64_t(w_nk ? N : K) * ldw * 2);
+  if (w_nk) return dispatch<false, false, EPI_ROPE>(a, w, C, nullptr, M, N, K, lda, ldw, ldc, 0, ab, wb, st, x);
+  return dispatch<false, true, EPI_ROPE>(a, w, C, nullptr, M, N, K, lda, ldw, ldc, 0, ab, wb, st, x);
 }
 
 }  // namespace mls

@@ -15,11 +15,20 @@
 // this wavefront's share of tile t+2) frees the stage of tile t+1, which is refilled at once with tile t+NS+1:
 // a tile is requested NS-1 = 3 iterations before it is read.
 //
-// LDS tile layouts are those of gemm_bf16_dma.hip ([row][k] with 64-byte rows, [k][col] with 512-byte k-rows, XOR
-// swizzled on the global-address side).  Restrictions, checked by the launcher: K (and the piece length of a
-// segmented contraction) a multiple of 32, so that no k-tile is ragged; everything else (ragged M and N) is
-// handled by out-of-range requests that zero-fill.  The launcher covers whole 256-column tiles; the column
-// remainder of a problem runs on the kernels of gemm_bf16_dma.hip.
+// LDS map: the four A stages (16 KiB each), then the four B stages.  A [k][col] tile has 512-byte k-rows, a B
+// [row][k] tile 64-byte rows, both XOR swizzled on the global-address side as in gemm_bf16_dma.hip.  An A operand
+// stored [row][k] is fetched differently: a 32-deep tile would take 64 bytes of every row, half a cache line, and the
+// other half would be fetched again one k-tile later (the L1 does not keep it that long), so that this operand
+// would cost twice its bytes in L1 fills.  Its k-tiles are therefore requested in pairs: one request covers 8 rows x
+// 128 bytes (whole lines), and the pair (tiles 2p, 2p+1) lands in the two adjacent stages as one [row][64 k] block
+// with 128-byte rows, the eight 16-byte chunks of a row permuted by (row >> 1) & 7 so that the fragment reads of
+// either k-tile are free of bank conflicts.  Pairs are requested in even iterations (12 requests: 8 of A, 4 of B),
+// odd iterations request B only (4).
+//
+// Restrictions, checked by the launcher: K (and the piece length of a segmented contraction) a multiple of 32, of
+// 64 when A is stored [row][k], so that no k-tile is ragged and no pair straddles the end; everything else (ragged
+// M and N) is handled by out-of-range requests that zero-fill.  The launcher covers whole 256-column tiles; the
+// column remainder of a problem runs on the kernels of gemm_bf16_dma.hip.
 #include <type_traits>
 
 #include "common.h"
@@ -31,8 +40,10 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) int i32x2;
 
 constexpr int BM = 256, BN = 256, BK = 32, NS = 4, NW = 4;
-constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-constexpr int LDS_BYTES = NS * STAGE;
+constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+constexpr int B_OFF = NS * A_BYTES;  // all A stages first, then all B stages
+constexpr int LDS_BYTES = NS * (A_BYTES + B_BYTES);
+constexpr int LDS_BYTES_NT = LDS_BYTES + 2 * B_BYTES;  // a [row][k] B has a ring of three pairs of stages
 constexpr uint32_t OOB = 0x80000000u;
 constexpr int MAX_SEGS = 16;
 
@@ -114,23 +125,34 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
   const int l16 = lane & 15, g4 = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(MLS_LDS unsigned char*)smem;
 
-  // ---- requests: 4 per operand per wavefront per k-tile; fixed per-lane byte offsets, the k-tile enters as a scalar
-  uint32_t goa[4], gob[4];
+  // ---- requests: 4 per operand per wavefront per k-tile (8 per pair of k-tiles for a [row][k] A); fixed per-lane
+  // byte offsets, the k-tile enters as a scalar
+  constexpr bool PAIR = !ATR, PAIRB = !BTR;
+  static_assert(!((PAIR || PAIRB) && SEG), "segmented contractions are the [k][col] form");
+  static_assert(PAIR || !PAIRB, "a [row][k] B comes with a [row][k] A only");
+  constexpr int NGA = PAIR ? 8 : 4, NGB = PAIRB ? 8 : 4;
+  uint32_t goa[NGA], gob[NGB];
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int q = wave * 4 + i;
+  for (int i = 0; i < NGA; i++) {
     if (ATR) {  // [k][col]: k-rows 2q, 2q+1; 32 chunks per k-row
+      const int q = wave * 4 + i;
       const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ ((kr & 3) << 2);
       goa[i] = m0 + c * 8 < M ? uint32_t((int64_t(kr) * lda + m0 + c * 8) * 2) : OOB;
-    } else {    // [row][k]: rows 16q .. 16q+15; 4 chunks per row
-      const int r = q * 16 + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
+    } else {    // [row][64 k]: rows 8q .. 8q+7; 8 chunks per row, LDS position p of a row holds chunk p ^ ((row >> 1) & 7)
+      const int q = wave * 8 + i;
+      const int r = q * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
       goa[i] = m0 + r < M ? uint32_t((int64_t(m0 + r) * lda + c * 8) * 2) : OOB;
     }
+  }
+#pragma unroll
+  for (int i = 0; i < NGB; i++) {
     if (BTR) {
+      const int q = wave * 4 + i;
       const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ ((kr & 3) << 2);
       gob[i] = n0 + c * 8 < N ? uint32_t((int64_t(kr) * ldb + n0 + c * 8) * 2) : OOB;
     } else {
-      const int r = q * 16 + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
+      const int q = wave * 8 + i;
+      const int r = q * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
       gob[i] = n0 + r < N ? uint32_t((int64_t(n0 + r) * ldb + c * 8) * 2) : OOB;
     }
   }
@@ -141,19 +163,33 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
   const i32x4 dead_a = make_rsrc(A, 0), dead_b = make_rsrc(B, 0);
   i32x4 ra = make_rsrc(SEG ? segs.a[0] : A, a_bytes), rb = make_rsrc(SEG ? segs.b[0] : B, b_bytes);
   int rq_tile = 0, rq_seg = 0, rq_in = 0;  // request cursor: next k-tile, its piece and its index inside the piece
-  // request D (0..7: four of A, four of B) of this wavefront for the next k-tile into `stage`
+  // request D of this wavefront for the cursor's k-tile into `stage`: D = 0..3 of A (unpaired form), 4..7 of B
   auto request = [&](int stage, auto DC) {
     constexpr int d = decltype(DC)::value;
     const bool live = rq_tile < nk;
-    const uint32_t la = lds0 + stage * STAGE + wave * 4096;
-    if constexpr (d < 4) dma16s(live ? ra : dead_a, goa[d], uint32_t(rq_in) * ka, la + d * 1024);
-    else dma16s(live ? rb : dead_b, gob[d - 4], uint32_t(rq_in) * kb, la + A_BYTES + (d - 4) * 1024);
+    if constexpr (d < 4) dma16s(live ? ra : dead_a, goa[d & (NGA - 1)], uint32_t(rq_in) * ka, lds0 + stage * A_BYTES + wave * 4096 + d * 1024);
+    else dma16s(live ? rb : dead_b, gob[(d - 4) & (NGB - 1)], uint32_t(rq_in) * kb, lds0 + B_OFF + stage * B_BYTES + wave * 4096 + (d - 4) * 1024);
   };
-  auto request_all = [&](int stage) {
-    request(stage, std::integral_constant<int, 0>{}); request(stage, std::integral_constant<int, 1>{});
-    request(stage, std::integral_constant<int, 2>{}); request(stage, std::integral_constant<int, 3>{});
-    request(stage, std::integral_constant<int, 4>{}); request(stage, std::integral_constant<int, 5>{});
-    request(stage, std::integral_constant<int, 6>{}); request(stage, std::integral_constant<int, 7>{});
+  // request D of this wavefront for the pair of k-tiles (2 pair, 2 pair + 1) of a [row][k] operand into stages 2 slot,
+  // 2 slot + 1: D = 0..7 of A, 8..15 of B
+  auto request_pair = [&](int slot, int pair, auto DC) {
+    constexpr int d = decltype(DC)::value;
+    if constexpr (d < 8)
+      dma16s(2 * pair < nk ? ra : dead_a, goa[d & (NGA - 1)], uint32_t(pair) * (4 * BK), lds0 + slot * (2 * A_BYTES) + wave * 8192 + d * 1024);
+    else
+      dma16s(2 * pair < nk ? rb : dead_b, gob[(d - 8) & (NGB - 1)], uint32_t(pair) * (4 * BK),
+             lds0 + B_OFF + slot + wave * 8192 + (d - 8) * 1024);  // (slot: a byte offset here)
+  };
+#define IC(n) std::integral_constant<int, n>{}
+  auto request_b_all = [&](int stage) { request(stage, IC(4)); request(stage, IC(5)); request(stage, IC(6)); request(stage, IC(7)); };
+  auto request_a_all = [&](int stage) { request(stage, IC(0)); request(stage, IC(1)); request(stage, IC(2)); request(stage, IC(3)); };
+  auto request_pair_all = [&](int slot, int pair) {
+    request_pair(slot, pair, IC(0)); request_pair(slot, pair, IC(1)); request_pair(slot, pair, IC(2)); request_pair(slot, pair, IC(3));
+    request_pair(slot, pair, IC(4)); request_pair(slot, pair, IC(5)); request_pair(slot, pair, IC(6)); request_pair(slot, pair, IC(7));
+  };
+  auto request_pairb_all = [&](int slot, int pair) {
+    request_pair(slot, pair, IC(8)); request_pair(slot, pair, IC(9)); request_pair(slot, pair, IC(10)); request_pair(slot, pair, IC(11));
+    request_pair(slot, pair, IC(12)); request_pair(slot, pair, IC(13)); request_pair(slot, pair, IC(14)); request_pair(slot, pair, IC(15));
   };
   auto advance = [&]() {
     rq_tile++;
@@ -167,46 +203,55 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
     }
   };
 
-  // ---- fragment addresses: absolute LDS byte addresses for stages 0 and 1 (`lo`) and for stages 2 and 3 (`hi` = lo +
-  // 64 KiB); stage parity and fragment index go into the read's immediate offset, so the loop holds no address
-  // arithmetic (and the compiler has no reason to recycle a fragment register while an MFMA may still read it).
-  // [row][k]: one address per operand, fragment i at +1024 i.  [k][col]: one address per fragment (the swizzle mixes
-  // with the fragment index), second half at +4 k-rows.
-  constexpr int NAA = ATR ? 8 : 1, NBA = BTR ? 8 : 1;
-  uint32_t fa_lo[NAA], fa_hi[NAA], fb_lo[NBA], fb_hi[NBA];
+  // ---- fragment addresses: absolute LDS byte addresses for stage 0; stage and fragment index go into the read's
+  // immediate offset, so the loop holds no address arithmetic (and the compiler has no reason to recycle a fragment
+  // register while an MFMA may still read it).
+  // [k][col]: one address per fragment (the swizzle mixes with the fragment index), second half at +4 k-rows.
+  // [row][64 k]: one address per k-tile of the pair (the permutation turns the step from one to the other into an
+  // XOR), fragment i at +2048 i.
+  constexpr int NAA = ATR ? 8 : 2, NBA = BTR ? 8 : 2;
+  uint32_t fa_b[NAA], fb_b[NBA];
   if (ATR) {
 #pragma unroll
     for (int i = 0; i < 8; i++) {
       const int kr = g4 * 8 + (l16 >> 2), col = wm + i * 16 + (l16 & 3) * 4;
-      fa_lo[i] = lds0 + kr * (BM * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
+      fa_b[i] = lds0 + kr * (BM * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
     }
   } else {
-    fa_lo[0] = lds0 + (wm + l16) * 64 + ((g4 ^ (l16 >> 2)) << 4);
+#pragma unroll
+    for (int hf = 0; hf < 2; hf++) fa_b[hf] = lds0 + (wm + l16) * 128 + (((hf * 4 + g4) ^ ((l16 >> 1) & 7)) << 4);
   }
   if (BTR) {
 #pragma unroll
     for (int j = 0; j < 8; j++) {
       const int kr = g4 * 8 + (l16 >> 2), col = wn + j * 16 + (l16 & 3) * 4;
-      fb_lo[j] = lds0 + A_BYTES + kr * (BN * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
+      fb_b[j] = lds0 + B_OFF + kr * (BN * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
     }
   } else {
-    fb_lo[0] = lds0 + A_BYTES + (wn + l16) * 64 + ((g4 ^ (l16 >> 2)) << 4);
+#pragma unroll
+    for (int hf = 0; hf < 2; hf++) fb_b[hf] = lds0 + B_OFF + (wn + l16) * 128 + (((hf * 4 + g4) ^ ((l16 >> 1) & 7)) << 4);
   }
-#pragma unroll
-  for (int i = 0; i < NAA; i++) fa_hi[i] = fa_lo[i] + 2 * STAGE;
-#pragma unroll
-  for (int j = 0; j < NBA; j++) fb_hi[j] = fb_lo[j] + 2 * STAGE;
   i32x4 fa[2][8], fb[2][8];
+  // A [row][k] B has a ring of three slots (pairs of stages), one more than A, so that its pairs can be requested a
+  // pair further ahead; 3 does not divide the loop's period of 4 iterations, so its slot is a run-time offset: b_slot
+  // is that of the pair being read, fb_cur the fragment addresses inside it (updated once per pair).
+  uint32_t b_slot = 0, b_free = 0;  // b_free: the slot read before b_slot, free for the next pair
+  uint32_t fb_cur[2] = {fb_b[0], fb_b[1]};
+  auto next_b_slot = [&]() {
+    b_free = b_slot;
+    b_slot = b_slot == 4 * B_BYTES ? 0 : b_slot + 2 * B_BYTES;
+    fb_cur[0] = fb_b[0] + b_slot;
+    fb_cur[1] = fb_b[1] + b_slot;
+  };
   // LDS read n (0..15; A fragments first) of the k-tile in stage ST into fragment set SET
   auto rd = [&](auto SETC, auto STC, auto NC) {
     constexpr int set = decltype(SETC)::value, st = decltype(STC)::value, n = decltype(NC)::value;
-    constexpr int so = (st & 1) * STAGE;
     if constexpr (n < 8) {
-      if constexpr (ATR) lds_read16_tr<so>(fa[set][n], st < 2 ? fa_lo[n] : fa_hi[n]);
-      else lds_read16<so + n * 1024>(fa[set][n], st < 2 ? fa_lo[0] : fa_hi[0]);
+      if constexpr (ATR) lds_read16_tr<st * A_BYTES>(fa[set][n], fa_b[n]);
+      else lds_read16<(st >> 1) * (2 * A_BYTES) + n * 2048>(fa[set][n], fa_b[st & 1]);
     } else {
-      if constexpr (BTR) lds_read16_tr<so>(fb[set][n - 8], st < 2 ? fb_lo[n - 8] : fb_hi[n - 8]);
-      else lds_read16<so + (n - 8) * 1024>(fb[set][n - 8], st < 2 ? fb_lo[0] : fb_hi[0]);
+      if constexpr (BTR) lds_read16_tr<st * B_BYTES>(fb[set][n - 8], fb_b[n - 8]);
+      else lds_read16<(n - 8) * 2048>(fb[set][n - 8], fb_cur[st & 1]);
     }
   };
 
@@ -217,62 +262,118 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
     for (int j = 0; j < 8; j++) c[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // ---- prologue: tiles 0 .. NS-1 requested; tile 0 read into set 0; tile 1 visible; tile NS requested into stage 0
+  // (its B only in the paired form: iteration 0 requests the pair 4, 5)
+  if constexpr (PAIRB) {  // B runs one pair further ahead than A
+    request_pair_all(0, 0); request_pairb_all(0, 0);
+    request_pair_all(1, 1); request_pairb_all(2 * B_BYTES, 1);
+    request_pairb_all(4 * B_BYTES, 2);
+    rq_tile = rq_in = NS;
+    wait_vmcnt<24>();
+  } else if constexpr (PAIR) {
+    request_pair_all(0, 0);
+    request_b_all(0); advance();
+    request_b_all(1); advance();
+    request_pair_all(1, 1);
+    request_b_all(2); advance();
+    request_b_all(3); advance();
+    wait_vmcnt<20>();
+  } else {
 #pragma unroll
-  for (int s = 0; s < NS; s++) {
-    request_all(s);
-    advance();
+    for (int s = 0; s < NS; s++) {
+      request_a_all(s);
+      request_b_all(s);
+      advance();
+    }
+    wait_vmcnt<(NS - 1) * 8>();
   }
-  wait_vmcnt<(NS - 1) * 8>();
   __syncthreads();
   {
-    using S0 = std::integral_constant<int, 0>;
-#define RD0(n) rd(S0{}, S0{}, std::integral_constant<int, n>{})
+#define RD0(n) rd(IC(0), IC(0), IC(n))
     RD0(0); RD0(1); RD0(2); RD0(3); RD0(4); RD0(5); RD0(6); RD0(7);
     RD0(8); RD0(9); RD0(10); RD0(11); RD0(12); RD0(13); RD0(14); RD0(15);
 #undef RD0
   }
-  wait_vmcnt<(NS - 2) * 8>();
+  wait_vmcnt<(NS - 2) * 8>();  // (both paired: tile 1 came with tile 0)
   wait_lgkm0();
   __syncthreads();
-  request_all(0);
+  if constexpr (!PAIR) request_a_all(0);
+  if constexpr (!PAIRB) request_b_all(0);
   advance();
 
   // iteration t (fragment set SET = t % 2): tile t+1 sits in stage ST = (t + 1) % NS
   auto iteration = [&](auto SETC, auto STC) {
     constexpr int set = decltype(SETC)::value, st = decltype(STC)::value;
+    if constexpr (PAIRB && (st & 1) == 0) next_b_slot();  // t odd: tile t+1 opens a new pair
     using SN = std::integral_constant<int, set ^ 1>;
     // first half: A fragments 0..3 against all of B, the 16 reads of tile t+1 in between
 #define MM(i, j) mfma16(c[i][j], fb[set][j], fa[set][i])
-#define RDN(n) rd(SN{}, STC, std::integral_constant<int, n>{})
+#define RDN(n) rd(SN{}, STC, IC(n))
 #define ROW_R(i, r0)                                                           \
   MM(i, 0); MM(i, 1); RDN(r0); MM(i, 2); MM(i, 3); RDN(r0 + 1);                \
   MM(i, 4); MM(i, 5); RDN(r0 + 2); MM(i, 6); MM(i, 7); RDN(r0 + 3);
     ROW_R(0, 0) ROW_R(1, 4) ROW_R(2, 8) ROW_R(3, 12)
 #undef ROW_R
-    wait_vmcnt<(NS - 2) * 8>();  // this wavefront's share of tile t+2 has landed
+    // this wavefront's share of tile t+2 has landed.  Unpaired: the requests of the last two iterations may be in
+    // flight.  Paired, t even: tile t+2's A came with the pair of iteration t-2, after which only 4 + 4 requests of B
+    // were issued; t odd: tile t+2 came with iteration t-3, followed by 4 + 12 requests.
+    // Both paired (A pairs are requested in even iterations, B pairs in odd ones): t even: tile t+2's A came with
+    // iteration t-2, its B with t-3, followed by the 8 requests of t-1; t odd: A came with t-3, B with t-4, followed
+    // by the requests of t-2 and t-1.
+    wait_vmcnt<PAIRB ? ((st & 1) ? 8 : 16) : PAIR ? ((st & 1) ? 8 : 16) : (NS - 2) * 8>();
     wait_lgkm0();                // its reads of tile t+1 are back
     __builtin_amdgcn_s_barrier();
-    // second half: A fragments 4..7, the 8 requests for tile t+NS+1 in between (one per four MFMAs)
-#define ROW_D(i, d0)                                                                              \
-  request(st, std::integral_constant<int, d0>{}); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3);         \
-  request(st, std::integral_constant<int, d0 + 1>{}); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
-    ROW_D(4, 0) ROW_D(5, 2) ROW_D(6, 4) ROW_D(7, 6)
+    // second half: A fragments 4..7 with the requests in between.  Unpaired: 8 for tile t+NS+1 (one per four MFMAs)
+    // into the stage just freed.  Paired, t even (ST odd): the pair (t+NS, t+NS+1) into stages ST-1, ST (tile t was read
+    // in iteration t-1, tile t+1 just now), then B of tile t+NS+1; t odd: B only.  Both paired, t even: the pair of A;
+    // t odd: the pair (t+5, t+6) of B into the slot of tiles t-1, t of its ring (read by the last barrier).
+    if constexpr (!PAIR) {
+#define ROW_D(i, d0)                                                        \
+  request(st, IC(d0)); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3);              \
+  request(st, IC(d0 + 1)); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
+      ROW_D(4, 0) ROW_D(5, 2) ROW_D(6, 4) ROW_D(7, 6)
 #undef ROW_D
+    } else if constexpr (PAIRB) {
+      const int pair = (rq_tile - 1) >> 1;
+#define ROW_P(i, d0) RQ(d0); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3); RQ(d0 + 1); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
+      if constexpr ((st & 1) != 0) {
+#define RQ(d) request_pair(st >> 1, pair, IC(d))
+        ROW_P(4, 0) ROW_P(5, 2) ROW_P(6, 4) ROW_P(7, 6)
+#undef RQ
+      } else {
+#define RQ(d) request_pair(b_free, pair + 1, IC(8 + d))
+        ROW_P(4, 0) ROW_P(5, 2) ROW_P(6, 4) ROW_P(7, 6)
+#undef RQ
+      }
+#undef ROW_P
+    } else if constexpr ((st & 1) != 0) {
+      const int pair = (rq_tile - 1) >> 1;
+#define RQP(d) request_pair(st >> 1, pair, IC(d))
+      RQP(0); MM(4, 0); MM(4, 1); MM(4, 2); RQP(1); MM(4, 3); MM(4, 4); MM(4, 5); RQP(2); MM(4, 6); MM(4, 7);
+      RQP(3); MM(5, 0); MM(5, 1); MM(5, 2); RQP(4); MM(5, 3); MM(5, 4); MM(5, 5); RQP(5); MM(5, 6); MM(5, 7);
+      RQP(6); MM(6, 0); MM(6, 1); MM(6, 2); RQP(7); MM(6, 3); MM(6, 4); MM(6, 5); request(st, IC(4)); MM(6, 6); MM(6, 7);
+      request(st, IC(5)); MM(7, 0); MM(7, 1); MM(7, 2); request(st, IC(6)); MM(7, 3); MM(7, 4); MM(7, 5); request(st, IC(7)); MM(7, 6); MM(7, 7);
+#undef RQP
+    } else {
+#define ROW_B(i, d) request(st, IC(d)); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
+      ROW_B(4, 4) ROW_B(5, 5) ROW_B(6, 6) ROW_B(7, 7)
+#undef ROW_B
+    }
 #undef RDN
 #undef MM
     advance();
   };
   // in groups of four (one turn of the stage ring): the tiles beyond the last one are zero-filled (descriptor of
   // length zero) and add nothing
+  // The compiler does not see MFMAs written as asm and inserts no wait states behind them; whatever it places at
+  // the loop exit (copies of accumulators) must find the last MFMA's result written: 16 idle cycles per turn.
   for (int t = 0; t < nk; t += 4) {
-    iteration(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-    iteration(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
-    iteration(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
-    iteration(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
-    // The compiler does not see MFMAs written as asm and inserts no wait states behind them; whatever it places at
-    // the loop exit (copies of accumulators) must find the last MFMA's result written: 16 idle cycles per turn.
+    iteration(IC(0), IC(1));
+    iteration(IC(1), IC(2));
+    iteration(IC(0), IC(3));
+    iteration(IC(1), IC(0));
     asm volatile("s_nop 15" ::: "memory");
   }
+#undef IC
   wait_vmcnt<0>();
   __syncthreads();
 
@@ -415,9 +516,10 @@ hipError_t launch16(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
   RopeArgs rp = {};
   if (rope) rp = *rope;
   static std::atomic<uint64_t> lds_raised{0};
-  if (hipError_t e = mls::raise_lds_limit(reinterpret_cast<const void*>(kern), LDS_BYTES, lds_raised)) return e;
+  constexpr int LDS = BTR ? LDS_BYTES : LDS_BYTES_NT;
+  if (hipError_t e = mls::raise_lds_limit(reinterpret_cast<const void*>(kern), LDS, lds_raised)) return e;
   const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(NW * 64), LDS_BYTES, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, tm, 0, X,
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(NW * 64), LDS, st, A, B, C, R, M, N, K, lda, ldb, ldc, ldr, ab, bb, tm, 0, X,
                      ldx, xf, sa, rp);
   return hipGetLastError();
 }
@@ -426,7 +528,8 @@ hipError_t launch16(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* R, 
 
 namespace mls {
 
-bool gemm_m16_ok(int K) { return K > 0 && K % BK == 0; }
+// k-tiles must be whole; an A stored [row][k] (NN, NT) is fetched in pairs of k-tiles
+bool gemm_m16_ok(int mode, int K) { return K > 0 && K % (mode == GEMM_TN ? BK : 2 * BK) == 0; }
 
 // C[M, N] (N a multiple of 256 or the whole problem) in one of the three modes; bf16 C (+ R) for NN and NT, fp32
 // C (+)= for TN.  Operand byte lengths as the DMA path takes them.
@@ -444,19 +547,25 @@ hipError_t gemm_m16(int mode, const void* A, const void* B, void* C, const void*
 }
 
 
-// GU[M, N = 2f] = A[M,K] W[K, 2f] (interleaved gate/up columns), Z[M, f] = silu(gate) * up; N a multiple of 256 here
+// GU[M, N = 2f] = A[M,K] W[K, 2f] (interleaved gate/up columns), Z[M, f] = silu(gate) * up; N a multiple of 256 here.
+// w_nk: W is given transposed, [2f][K] with row stride ldw.
 hipError_t gemm_m16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int N, int K, int64_t lda, int64_t ldw,
-                           int64_t ldgu, int64_t ldz, uint32_t ab, uint32_t bb, hipStream_t st) {
-  return launch16<false, true, E_SWIGLU, false>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), GU, nullptr, M, N, K,
-                                                lda, ldw, ldgu, 0, ab, bb, st, nullptr, Z, ldz, 0, nullptr);
+                           int64_t ldgu, int64_t ldz, uint32_t ab, uint32_t bb, hipStream_t st, bool w_nk) {
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  if (w_nk) return launch16<false, false, E_SWIGLU, false>(a, w, GU, nullptr, M, N, K, lda, ldw, ldgu, 0, ab, bb, st, nullptr, Z, ldz, 0, nullptr);
+  return launch16<false, true, E_SWIGLU, false>(a, w, GU, nullptr, M, N, K, lda, ldw, ldgu, 0, ab, bb, st, nullptr, Z, ldz, 0, nullptr);
 }
-// C[M, N] = A[M,K] W[K,N] with the head vectors in the columns below rot_cols rotated by the angle of their row's position
+// C[M, N] = A[M,K] W[K,N] with the head vectors in the columns below rot_cols rotated by the angle of their row's
+// position.  w_nk: W is given transposed, [N][K] with row stride ldw.
 hipError_t gemm_m16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
                          uint32_t ab, uint32_t bb, const float* cos_tab, const float* sin_tab, int seq, int rot_cols,
-                         int head_dim, hipStream_t st) {
+                         int head_dim, hipStream_t st, bool w_nk) {
   const RopeArgs ra = {cos_tab, sin_tab, seq, rot_cols, head_dim};
-  return launch16<false, true, E_ROPE, false>(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), C, nullptr, M, N, K, lda,
-                                              ldw, ldc, 0, ab, bb, st, nullptr, nullptr, 0, 0, &ra);
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  if (w_nk) return launch16<false, false, E_ROPE, false>(a, w, C, nullptr, M, N, K, lda, ldw, ldc, 0, ab, bb, st, nullptr, nullptr, 0, 0, &ra);
+  return launch16<false, true, E_ROPE, false>(a, w, C, nullptr, M, N, K, lda, ldw, ldc, 0, ab, bb, st, nullptr, nullptr, 0, 0, &ra);
 }
 
 // C[M, N] (+)= sum_i A_i[kseg, M]^T B_i[kseg, N] in fp32 over nseg <= 16 pieces (kseg a multiple of 32), N a multiple

@@ -45,14 +45,15 @@ hipError_t gemm_bf16_tn_segments(const void* const* A, const void* const* B, int
                                  int64_t lda, int64_t ldb, int64_t ldc, hipStream_t st, int gu_f = 0,
                                  bool overwrite = false);
 // the 256x256 tiles of a problem on the 16x16x32 form of the matrix instruction (gemm_bf16_m16.hip); K % 32 == 0
-bool gemm_m16_ok(int K);
+// (% 64 for NN and NT)
+bool gemm_m16_ok(int mode, int K);
 hipError_t gemm_m16(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, uint32_t ab, uint32_t bb, hipStream_t st);
 hipError_t gemm_m16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int N, int K, int64_t lda, int64_t ldw,
-                           int64_t ldgu, int64_t ldz, uint32_t ab, uint32_t bb, hipStream_t st);
+                           int64_t ldgu, int64_t ldz, uint32_t ab, uint32_t bb, hipStream_t st, bool w_nk);
 hipError_t gemm_m16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
                          uint32_t ab, uint32_t bb, const float* cos_tab, const float* sin_tab, int seq, int rot_cols,
-                         int head_dim, hipStream_t st);
+                         int head_dim, hipStream_t st, bool w_nk);
 hipError_t gemm_m16_tn_segments(const void* const* A, const void* const* B, int nseg, void* C, int M, int N, int kseg,
                                 int64_t lda, int64_t ldb, int64_t ldc, uint32_t ab, uint32_t bb, hipStream_t st, int gu_f,
                                 bool overwrite);
@@ -60,15 +61,18 @@ hipError_t fill_zero_f32(float* p, size_t n, hipStream_t st);
 // SwiGLU fused into the gate/up contraction (bf16, f % 32 == 0, DMA path).  Interleaved gate/up column order:
 // 32 gate columns, the 32 up columns of the same indices, and so on (gu_interleaved_col in common.h).
 //   GU[M, 2f] = A[M,K] W[K, 2f] (W and GU interleaved), Z[M, f] = silu(gate) * up
-bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw);
+// w_nk: W is given transposed, [2f][K] (rows in the interleaved order) with row stride ldw.
+bool gemm_swiglu_ok(int M, int f, int K, int64_t lda, int64_t ldw, bool w_nk = false);
 hipError_t gemm_bf16_swiglu(const void* A, const void* W, void* GU, void* Z, int M, int f, int K, int64_t lda,
-                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st);
+                            int64_t ldw, int64_t ldgu, int64_t ldz, hipStream_t st, bool w_nk = false);
 // The rotary embedding fused into the q|k|v projection (bf16, DMA path): C[M, N] = A[M,K] W[K,N] rounded to bf16, then
 // every head vector (head_dim = 64 or 128 columns) in the columns below rot_cols rotated by the angle of its row's
 // position row % seq, pairs (i, i + head_dim/2); cos_tab, sin_tab: [seq][head_dim/2] fp32.
-bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim);
+// w_nk: W is given transposed, [N][K] with row stride ldw.
+bool gemm_rope_ok(int M, int N, int K, int64_t lda, int64_t ldw, int seq, int rot_cols, int head_dim, bool w_nk = false);
 hipError_t gemm_bf16_rope(const void* A, const void* W, void* C, int M, int N, int K, int64_t lda, int64_t ldw, int64_t ldc,
-                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st);
+                          const float* cos_tab, const float* sin_tab, int seq, int rot_cols, int head_dim, hipStream_t st,
+                          bool w_nk = false);
 hipError_t gemm_f32(int mode, const void* A, const void* B, void* C, const void* R, int M, int N, int K, int64_t lda,
                     int64_t ldb, int64_t ldc, int64_t ldr, hipStream_t st);
 
