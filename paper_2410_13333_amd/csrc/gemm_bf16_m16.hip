@@ -104,6 +104,12 @@ __device__ __forceinline__ void lds_read16_tr(i32x4& f, uint32_t addr) {
   f = i32x4{lo[0], lo[1], hi[0], hi[1]};  // (the two halves are allocated as one register quad: no copies)
 }
 
+// [k][col] tiles: XOR applied to the 16-byte chunk index (0..31) of k-row kr.  A transposing 8-byte read takes, per
+// group of 16 lanes, 32 bytes from each of k-rows kr0 .. kr0+3, and 32 lanes (two groups, k-rows 8 apart) go through
+// the 64 banks together; k-rows lie 512 bytes = two bank rounds apart, so the eight 32-byte pieces must be moved to
+// eight different places of a round: bits 2, 3 from kr & 3, bit 1 from bit 3 of kr.
+__device__ __forceinline__ constexpr int swz_kcol(int kr) { return ((kr & 3) << 2) | (((kr >> 3) & 1) << 1); }
+
 template <bool ATR, bool BTR, int EPI, bool SEG>
 __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                          void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
   for (int i = 0; i < NGA; i++) {
     if (ATR) {  // [k][col]: k-rows 2q, 2q+1; 32 chunks per k-row
       const int q = wave * 4 + i;
-      const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ ((kr & 3) << 2);
+      const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ swz_kcol(kr);
       goa[i] = m0 + c * 8 < M ? uint32_t((int64_t(kr) * lda + m0 + c * 8) * 2) : OOB;
     } else {    // [row][64 k]: rows 8q .. 8q+7; 8 chunks per row, LDS position p of a row holds chunk p ^ ((row >> 1) & 7)
       const int q = wave * 8 + i;
@@ -148,7 +154,7 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
   for (int i = 0; i < NGB; i++) {
     if (BTR) {
       const int q = wave * 4 + i;
-      const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ ((kr & 3) << 2);
+      const int kr = q * 2 + (lane >> 5), c = (lane & 31) ^ swz_kcol(kr);
       gob[i] = n0 + c * 8 < N ? uint32_t((int64_t(kr) * ldb + n0 + c * 8) * 2) : OOB;
     } else {
       const int q = wave * 8 + i;
@@ -215,7 +221,7 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
 #pragma unroll
     for (int i = 0; i < 8; i++) {
       const int kr = g4 * 8 + (l16 >> 2), col = wm + i * 16 + (l16 & 3) * 4;
-      fa_b[i] = lds0 + kr * (BM * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
+      fa_b[i] = lds0 + kr * (BM * 2) + (((col >> 3) ^ swz_kcol(kr)) << 4) + (col & 7) * 2;
     }
   } else {
 #pragma unroll
@@ -225,7 +231,7 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
 #pragma unroll
     for (int j = 0; j < 8; j++) {
       const int kr = g4 * 8 + (l16 >> 2), col = wn + j * 16 + (l16 & 3) * 4;
-      fb_b[j] = lds0 + B_OFF + kr * (BN * 2) + (((col >> 3) ^ ((kr & 3) << 2)) << 4) + (col & 7) * 2;
+      fb_b[j] = lds0 + B_OFF + kr * (BN * 2) + (((col >> 3) ^ swz_kcol(kr)) << 4) + (col & 7) * 2;
     }
   } else {
 #pragma unroll
