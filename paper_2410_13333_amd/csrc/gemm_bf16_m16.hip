@@ -11,25 +11,33 @@
 // registers, all in AGPRs.  k-tiles are 32 deep (one MFMA's depth), NS = 4 stages of 32 KiB in LDS, filled by
 // buffer_load_dwordx4 ... lds.  The fragments of a whole k-tile (8 of A, 8 of B, 16 bytes per lane each) live in
 // registers, in two sets: iteration t issues the MFMAs of tile t from one set while the LDS reads of tile t+1
-// fill the other, so no MFMA ever waits for LDS.  In the middle of the iteration one barrier (after waiting for
-// this wavefront's share of tile t+2) frees the stage of tile t+1, which is refilled at once with tile t+NS+1:
-// a tile is requested NS-1 = 3 iterations before it is read.
+// fill the other, so no MFMA ever waits for LDS.  One barrier per iteration (after waiting for this wavefront's
+// share of tile t+2) frees the stage of tile t+1, which is refilled at once with tile t+NS+1: a tile is requested
+// NS-1 = 3 iterations before it is read.
 //
-// LDS map: the four A stages (16 KiB each), then the four B stages.  A [k][col] tile has 512-byte k-rows, a B
-// [row][k] tile 64-byte rows, both XOR swizzled on the global-address side as in gemm_bf16_dma.hip.  An A operand
-// stored [row][k] is fetched differently: a 32-deep tile would take 64 bytes of every row, half a cache line, and the
-// other half would be fetched again one k-tile later (the L1 does not keep it that long), so that this operand
-// would cost twice its bytes in L1 fills.  Its k-tiles are therefore requested in pairs: one request covers 8 rows x
-// 128 bytes (whole lines), and the pair (tiles 2p, 2p+1) lands in the two adjacent stages as one [row][64 k] block
-// with 128-byte rows, the eight 16-byte chunks of a row permuted by (row >> 1) & 7 so that the fragment reads of
-// either k-tile are free of bank conflicts.  Pairs are requested in even iterations (12 requests: 8 of A, 4 of B),
-// odd iterations request B only (4).
+// LDS map: the A stages (16 KiB each), then the B stages.  A [k][col] tile has 512-byte k-rows, XOR swizzled on the
+// global-address side (swz_kcol).  An operand stored [row][k] is fetched differently: a 32-deep tile would take 64
+// bytes of every row, half a cache line, and the other half would be fetched again one k-tile later (the L1 does
+// not keep it that long).  Its k-tiles are therefore requested in pairs: one request covers 8 rows x 128 bytes
+// (whole lines), and the pair (tiles 2p, 2p+1) lands in two adjacent stages as one [row][64 k] block with 128-byte
+// rows, the eight 16-byte chunks of a row permuted by (row >> 1) & 7 so that the fragment reads (plain 16-byte
+// reads) of either k-tile are free of bank conflicts.  Request schedules, per wavefront:
+//   TN (both [k][col])          8 per iteration (4 of A, 4 of B)
+//   NN (A [row][k])             even iterations 12 (the pair of A, 4 of B), odd ones 4 (B)
+//   NT (both [row][k])          8 per iteration: the pair of A in even iterations, the pair of B in odd ones; B has a
+//                               ring of three pair slots (160 KiB of LDS in all) so that it runs a pair further ahead
+//                               (3 does not divide the loop's period of 4: its slot is a run-time offset).
+// What was measured on the 7B layer's shapes (TFLOP/s, random operands): pairing A alone lifted NT from 1330 to 1410;
+// pairing B as well with all 16 requests in the even iterations fell back to 1375 (bursts stall the in-order issue
+// of the wavefront), alternating A and B pairs reached 1460.  NT is now the fastest form (NN 1350, TN 1410), so
+// the layer runs its forward products against transposed weight copies.
 //
 // Restrictions, checked by the launcher: K (and the piece length of a segmented contraction) a multiple of 32, of
 // 64 when A is stored [row][k], so that no k-tile is ragged and no pair straddles the end; everything else (ragged
 // M and N) is handled by out-of-range requests that zero-fill.  The launcher covers whole 256-column tiles; the
 // column remainder of a problem runs on the kernels of gemm_bf16_dma.hip.
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 #include "kernels.h"
@@ -48,6 +56,19 @@ constexpr uint32_t OOB = 0x80000000u;
 constexpr int MAX_SEGS = 16;
 
 enum { E_BF16 = 0, E_F32 = 1, E_SWIGLU = 2, E_ROPE = 3 };
+// The row of MFMAs (of 8) of an iteration before which the barrier sits.  The LDS reads are spread over rows 0..3;
+// with the barrier one row later the last reads are back when the wavefront gets there (measured: 5 is 1 % faster
+// than 4 for the [k][col] forms, 6 is 2 % slower for all: the requests then crowd into two rows).
+constexpr int ROW2 = 5;
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 struct SegArgs {
   const bf16_t* a[MAX_SEGS];
@@ -319,6 +340,8 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
   MM(i, 4); MM(i, 5); RDN(r0 + 2); MM(i, 6); MM(i, 7); RDN(r0 + 3);
     ROW_R(0, 0) ROW_R(1, 4) ROW_R(2, 8) ROW_R(3, 12)
 #undef ROW_R
+    // (the reads are all issued by now; ROW2 - 4 more rows of MFMAs cover the latency of the last ones)
+    static_for<(ROW2 - 4) * 8>([&](auto MC) { MM(4 + decltype(MC)::value / 8, decltype(MC)::value % 8); });
     // this wavefront's share of tile t+2 has landed.  Unpaired: the requests of the last two iterations may be in
     // flight.  Paired, t even: tile t+2's A came with the pair of iteration t-2, after which only 4 + 4 requests of B
     // were issued; t odd: tile t+2 came with iteration t-3, followed by 4 + 12 requests.
@@ -328,42 +351,30 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
     wait_vmcnt<PAIRB ? ((st & 1) ? 8 : 16) : PAIR ? ((st & 1) ? 8 : 16) : (NS - 2) * 8>();
     wait_lgkm0();                // its reads of tile t+1 are back
     __builtin_amdgcn_s_barrier();
-    // second half: A fragments 4..7 with the requests in between.  Unpaired: 8 for tile t+NS+1 (one per four MFMAs)
-    // into the stage just freed.  Paired, t even (ST odd): the pair (t+NS, t+NS+1) into stages ST-1, ST (tile t was read
-    // in iteration t-1, tile t+1 just now), then B of tile t+NS+1; t odd: B only.  Both paired, t even: the pair of A;
-    // t odd: the pair (t+5, t+6) of B into the slot of tiles t-1, t of its ring (read by the last barrier).
-    if constexpr (!PAIR) {
-#define ROW_D(i, d0)                                                        \
-  request(st, IC(d0)); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3);              \
-  request(st, IC(d0 + 1)); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
-      ROW_D(4, 0) ROW_D(5, 2) ROW_D(6, 4) ROW_D(7, 6)
-#undef ROW_D
-    } else if constexpr (PAIRB) {
-      const int pair = (rq_tile - 1) >> 1;
-#define ROW_P(i, d0) RQ(d0); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3); RQ(d0 + 1); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
-      if constexpr ((st & 1) != 0) {
-#define RQ(d) request_pair(st >> 1, pair, IC(d))
-        ROW_P(4, 0) ROW_P(5, 2) ROW_P(6, 4) ROW_P(7, 6)
-#undef RQ
-      } else {
-#define RQ(d) request_pair(b_free, pair + 1, IC(8 + d))
-        ROW_P(4, 0) ROW_P(5, 2) ROW_P(6, 4) ROW_P(7, 6)
-#undef RQ
-      }
-#undef ROW_P
-    } else if constexpr ((st & 1) != 0) {
-      const int pair = (rq_tile - 1) >> 1;
-#define RQP(d) request_pair(st >> 1, pair, IC(d))
-      RQP(0); MM(4, 0); MM(4, 1); MM(4, 2); RQP(1); MM(4, 3); MM(4, 4); MM(4, 5); RQP(2); MM(4, 6); MM(4, 7);
-      RQP(3); MM(5, 0); MM(5, 1); MM(5, 2); RQP(4); MM(5, 3); MM(5, 4); MM(5, 5); RQP(5); MM(5, 6); MM(5, 7);
-      RQP(6); MM(6, 0); MM(6, 1); MM(6, 2); RQP(7); MM(6, 3); MM(6, 4); MM(6, 5); request(st, IC(4)); MM(6, 6); MM(6, 7);
-      request(st, IC(5)); MM(7, 0); MM(7, 1); MM(7, 2); request(st, IC(6)); MM(7, 3); MM(7, 4); MM(7, 5); request(st, IC(7)); MM(7, 6); MM(7, 7);
-#undef RQP
-    } else {
-#define ROW_B(i, d) request(st, IC(d)); MM(i, 0); MM(i, 1); MM(i, 2); MM(i, 3); MM(i, 4); MM(i, 5); MM(i, 6); MM(i, 7);
-      ROW_B(4, 4) ROW_B(5, 5) ROW_B(6, 6) ROW_B(7, 7)
-#undef ROW_B
-    }
+    // second part: the remaining A fragments with the requests spread evenly in between.  Unpaired: 8 for tile
+    // t+NS+1 into the stage just freed.  Paired, t even (ST odd): the pair (t+NS, t+NS+1) into stages ST-1, ST (tile t
+    // was read in iteration t-1, tile t+1 just now), then B of tile t+NS+1; t odd: B only.  Both paired, t even: the
+    // pair of A; t odd: the pair (t+5, t+6) of B into the slot of tiles t-1, t of its ring (read by the last barrier).
+    const int pair = (rq_tile - 1) >> 1;
+    constexpr bool even = (st & 1) != 0;
+    constexpr int nreq = !PAIR ? 8 : PAIRB ? 8 : even ? 12 : 4;
+    auto rqn = [&](auto NC) {
+      constexpr int n = decltype(NC)::value;
+      if constexpr (!PAIR) request(st, IC(n));
+      else if constexpr (PAIRB && even) request_pair(st >> 1, pair, IC(n));
+      else if constexpr (PAIRB) request_pair(b_free, pair + 1, IC(8 + n));
+      else if constexpr (even && n < 8) request_pair(st >> 1, pair, IC(n));
+      else if constexpr (even) request(st, IC(n - 4));
+      else request(st, IC(4 + n));
+    };
+    constexpr int slots = (8 - ROW2) * 8;
+    static_for<slots>([&](auto MC) {
+      constexpr int m = decltype(MC)::value;
+      static_for<nreq>([&](auto RC) {
+        if constexpr ((decltype(RC)::value * slots) / nreq == m) rqn(RC);
+      });
+      MM(ROW2 + m / 8, m % 8);
+    });
 #undef RDN
 #undef MM
     advance();
