@@ -36,6 +36,33 @@ def test_bf16_three_modes(M, N, K):
     assert rel_err(to_host64(acc), 0.5 + 2 * (a64 @ b64)) < 1e-5
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 4096, 64), (4096, 4096, 128), (4096, 4096, 192), (4096, 4096, 320),
+                                   (4000, 4104, 448), (4096, 4096, 32), (4088, 4096, 160)])
+def test_bf16_16x16x32_kernel_at_awkward_depths(M, N, K):
+    """At least 256 tiles of 256x256, so that the problem runs on the 16x16x32 kernel: contraction depths of one to a
+    few k-tiles (prologue with nothing behind it, rings that do not come round, a k-tile count that is no multiple of
+    the loop's period), ragged last tile rows, a column remainder beside it.  K % 64 != 0 exercises only the TN form
+    there; the other two then run on the 32x32x16 kernels."""
+    import torch
+    import paper_2410_13333_amd as mls
+    g = torch.Generator(device="cpu").manual_seed(M + 3 * N + 7 * K)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    b = torch.randn(K, N, generator=g).to(torch.bfloat16).cuda()
+    r = torch.randn(M, N, generator=g).to(torch.bfloat16).cuda()
+    ref = to_host64(a) @ to_host64(b)
+    c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    mls.gemm(0, a, b, c, r)
+    assert rel_err(to_host64(c), ref + to_host64(r)) < 4e-3
+    mls.gemm(1, a, b.t().contiguous(), c)
+    assert rel_err(to_host64(c), ref) < 4e-3
+    acc = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    at = a.t().contiguous()
+    mls.gemm(2, at, b, acc)
+    mls.gemm(2, at, b, acc)
+    torch.cuda.synchronize()
+    assert rel_err(to_host64(acc), 0.5 + 2 * ref) < 1e-5
+
+
 def test_fp32_three_modes():
     import torch
     import paper_2410_13333_amd as mls
