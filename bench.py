@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# HBM bytes per GEMM launch (average over all gemm_dma_kernel dispatches of a step), from the rocprofv3 --pmc
+# HBM bytes per GEMM launch (average over all gemm16_kernel and gemm_dma_kernel dispatches of a step), from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/stage_7b_4x4_hbm_traffic.txt:
 # (2.0 * 363007 KiB fetched + 1.0 * 79347 KiB written) * 1024.  Only valid for the default workload.
 PROFILED_GEMM_TRAFFIC = {"7b": 8.25e8}
@@ -258,10 +258,11 @@ def run_gemm(steps, warmup, data):
     import torch
     import paper_2410_13333_amd as mls
     T = 4096
-    shapes = {0: [(T, 12288, 4096), (T, 4096, 4096), (T, 22016, 4096), (T, 4096, 11008)],
-              1: [(T, 11008, 4096), (T, 4096, 22016), (T, 4096, 4096), (T, 4096, 12288)],
-              2: [(11008, 4096, 4 * T), (4096, 22016, 4 * T), (4096, 4096, 4 * T), (4096, 12288, 4 * T)]}
-    names = {0: "forward (NN)", 1: "data gradient (NT)", 2: "weight gradient (TN)"}
+    # (mode, M, N, K): as the stage runs them, the forward products in the NT form against transposed weight copies
+    groups = {"forward (NT on W^T)": [(1, T, 12288, 4096), (1, T, 4096, 4096), (1, T, 22016, 4096), (1, T, 4096, 11008)],
+              "data gradient (NT on W)": [(1, T, 11008, 4096), (1, T, 4096, 22016), (1, T, 4096, 4096), (1, T, 4096, 12288)],
+              "weight gradient (TN)": [(2, 11008, 4096, 4 * T), (2, 4096, 22016, 4 * T), (2, 4096, 4096, 4 * T),
+                                       (2, 4096, 12288, 4 * T)]}
     g = torch.Generator(device="cuda").manual_seed(5)
 
     def operand(r, c):  # row-padded like the library's internal layout
@@ -278,9 +279,9 @@ def run_gemm(steps, warmup, data):
             raise SystemExit("--data must be randn, zeros, ones or bits")
         return t.to(torch.bfloat16)[:, :c]
     per_mode, tot_ms, tot_fl = {}, 0.0, 0.0
-    for mode in (0, 1, 2):
+    for name, shapes in groups.items():
         ms_mode = fl_mode = 0.0
-        for (M, N, K) in shapes[mode]:
+        for (mode, M, N, K) in shapes:
             a = operand(M, K) if mode != 2 else operand(K, M)
             b = operand(K, N) if mode != 1 else operand(N, K)
             c = torch.zeros(M, N + 64, device="cuda", dtype=torch.float32 if mode == 2 else torch.bfloat16)[:, :N]
@@ -295,7 +296,7 @@ def run_gemm(steps, warmup, data):
             torch.cuda.synchronize()
             ms_mode += e0.elapsed_time(e1) / steps
             fl_mode += 2.0 * M * N * K
-        per_mode[names[mode]] = {"ms": ms_mode, "tflops": fl_mode / (ms_mode * 1e-3) / 1e12}
+        per_mode[name] = {"ms": ms_mode, "tflops": fl_mode / (ms_mode * 1e-3) / 1e12}
         tot_ms += ms_mode
         tot_fl += fl_mode
     tf = tot_fl / (tot_ms * 1e-3) / 1e12
@@ -303,7 +304,7 @@ def run_gemm(steps, warmup, data):
             "warmup": warmup, "ms_per_step": tot_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": f"synthetic ({data})",
             "config": {"workload": "the 12 contractions of one 7B layer x micro-batch, 4096 tokens, stand-alone launches"},
-            "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
+            "roofline": {"bound": "mfma", "kernel": "gemm16_kernel", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
                          "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
             "per_mode": per_mode}
 
@@ -407,7 +408,7 @@ def main():
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "tau_ms_per_layer_microbatch": ms / (K * M),
         "model_flops_per_step": flops_step,
-        "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm16_kernel (256x256 tiles) + gemm_dma_kernel (column remainders)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": PROFILED_GEMM_TRAFFIC.get(a.workload),
                      "flops_per_launch": gemm_flops_launch, "avg_launch_ms": gemm_ms / gemm_n},
         "kernel_classes": classes,
