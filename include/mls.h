@@ -145,7 +145,9 @@ size_t mls_stage_grad_elems(const mls_stage* s);
  * mls_optim.h); workspace_bytes does not grow with the layer count. */
 typedef struct {
   size_t total_bytes;                       /* = param_bytes + stash_bytes + workspace_bytes              */
-  size_t param_bytes;                       /* max_layers layers, storage type, internal row-padded layout */
+  size_t param_bytes;                       /* max_layers layers, storage type, internal row-padded layout;
+                                               bf16: plus the transposed copy of the four matrices of a layer
+                                               that the forward products read                               */
   size_t stash_bytes;                       /* max_inflight * max_layers entries                           */
   size_t workspace_bytes;                   /* backward workspace, recomputation scratch, rotary tables    */
   size_t param_bytes_per_layer;
