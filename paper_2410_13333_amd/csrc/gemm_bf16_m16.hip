@@ -425,6 +425,48 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
     unsigned char* ws = smem + wave * 8192;
     unsigned char* wz = ws + 4096;
     bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+    // E_ROPE: the rotary table entries of a block of 16 rows (16 positions x head_dim/2 cosines and sines, fp32) come
+    // through LDS as well: requested by buffer_load ... lds two blocks ahead into a ring of three slots per wavefront
+    // (cos 4 KiB | sin 4 KiB each, behind the staging areas), read back as 16 bytes per lane.  The wavefront is alone
+    // on its SIMD here: as plain loads, used right away, the entries cost their full latency in every block (48 us per
+    // launch at the 7B shape), and held in registers ahead of time they spill.  A row of a slot keeps its 16-byte
+    // chunks XORed with the row index (bank conflicts), applied on the global-address side.
+    const bool use_rope = EPI == E_ROPE && col0 + int(ccol0) < rope.rot_cols;  // wave-uniform: whole heads; v is not rotated
+    constexpr int RING0 = 32768, RING_SLOT = 8192;
+    const uint32_t ring = lds0 + RING0 + wave * (3 * RING_SLOT);
+    const unsigned char* ringp = smem + RING0 + wave * (3 * RING_SLOT);
+    i32x4 cos_src = {}, sin_src = {};
+    int p0 = 0;
+    if constexpr (EPI == E_ROPE) {
+      const uint32_t tab_bytes = uint32_t(rope.seq) * uint32_t(rope.head_dim / 2) * 4u;
+      cos_src = make_rsrc(rope.cos_tab, tab_bytes);
+      sin_src = make_rsrc(rope.sin_tab, tab_bytes);
+      p0 = int(crow0 % rope.seq);
+    }
+    // TP = MFMA tiles between the halves of a rotary pair (head_dim / 32); a table row is 64 TP bytes = 4 TP chunks
+    auto rope_request = [&](int i, auto TPC) {
+      constexpr int TP = decltype(TPC)::value, CPR = 4 * TP, RPI = 16 / TP;  // chunks per row, rows per request
+#pragma unroll
+      for (int q = 0; q < TP; q++) {
+        const int r = q * RPI + lane / CPR;  // row of the block
+        int pos = p0 + i * 16 + r;           // its position in the sequence
+        if (rope.seq >= 128) pos = pos >= rope.seq ? pos - rope.seq : pos;
+        else pos = pos % rope.seq;
+        const int sw = TP == 4 ? r : (r >> 1) & 7;
+        const uint32_t off = crow0 + i * 16 + r < M ? uint32_t(pos * (64 * TP) + (((lane % CPR) ^ sw) << 4)) : OOB;
+        dma16s(cos_src, off, 0, ring + (i % 3) * RING_SLOT + q * 1024);
+        dma16s(sin_src, off, 0, ring + (i % 3) * RING_SLOT + 4096 + q * 1024);
+      }
+    };
+    auto rope_request_any = [&](int i) {
+      if (rope.head_dim == 128) rope_request(i, std::integral_constant<int, 4>{}); else rope_request(i, std::integral_constant<int, 2>{});
+    };
+    if constexpr (EPI == E_ROPE) {
+      if (use_rope) {
+        rope_request_any(0);
+        rope_request_any(1);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 8; i++) {
       const int64_t row = crow0 + i * 16 + l16;
@@ -447,22 +489,23 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
         }
       }
       if constexpr (EPI == E_ROPE) {
-        // TP = MFMA tiles between the halves of a pair (head_dim / 32)
         auto rotate = [&](auto TPC) {
           constexpr int TP = decltype(TPC)::value;
-          const int d2 = TP * 16;
-          const int64_t at = int64_t((row < M ? row : 0) % rope.seq) * d2 + g4 * 4;
+          if (i + 2 < 8) rope_request(i + 2, TPC);
+          // the requests of block i are older than those of blocks i+1 and i+2 (2 TP each) and than every store in
+          // between, which can only make this wait longer than needed
+          if (i + 2 < 8) wait_vmcnt<4 * TP>();
+          else if (i + 1 < 8) wait_vmcnt<2 * TP>();
+          else wait_vmcnt<0>();
+          const int sw = TP == 4 ? l16 : (l16 >> 1) & 7;
+          const unsigned char* slot = ringp + (i % 3) * RING_SLOT + l16 * (64 * TP);
 #pragma unroll
           for (int j = 0; j < 8; j++) {
-            if constexpr (true) {
-              if ((j % (2 * TP)) >= TP) continue;                                   // second halves go with their firsts
-              if (col0 + int(ccol0) + j * 16 >= rope.rot_cols) continue;           // whole heads: v is not rotated
-              constexpr int dummy = 0; (void)dummy;
-            }
-            const int jp = (j + TP) & 7;
-            const int fi = (j % TP) * 16;                                           // feature index of the tile's first column
-            const float4 cs = *reinterpret_cast<const float4*>(rope.cos_tab + at + fi);
-            const float4 sn = *reinterpret_cast<const float4*>(rope.sin_tab + at + fi);
+            if ((j % (2 * TP)) >= TP) continue;  // second halves go with their firsts
+            const int jp = j + TP;
+            const int ch = ((j % TP) * 4 + g4) ^ sw;  // chunk of features 16 (j % TP) + 4 g4 .. +3
+            const float4 cs = *reinterpret_cast<const float4*>(slot + (ch << 4));
+            const float4 sn = *reinterpret_cast<const float4*>(slot + 4096 + (ch << 4));
             const float cc[4] = {cs.x, cs.y, cs.z, cs.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
 #pragma unroll
             for (int e = 0; e < 4; e++) {
@@ -472,7 +515,9 @@ __global__ __launch_bounds__(NW * 64) void gemm16_kernel(const bf16_t* __restric
             }
           }
         };
-        if (rope.head_dim == 128) rotate(std::integral_constant<int, 4>{}); else rotate(std::integral_constant<int, 2>{});
+        if (use_rope) {
+          if (rope.head_dim == 128) rotate(std::integral_constant<int, 4>{}); else rotate(std::integral_constant<int, 2>{});
+        }
       }
 #pragma unroll
       for (int j = 0; j < 8; j++) {
