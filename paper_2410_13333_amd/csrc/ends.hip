@@ -213,6 +213,9 @@ struct mls_ends {
   int64_t ld_h, ld_v;
   size_t off_e, off_g, off_w, n_params;  // public offsets (= layout of grads)
   char *embed = nullptr, *gamma = nullptr, *wlm = nullptr;  // internal: embed [V, ld_h], gamma [h], w_lm [h, ld_v]
+  // bf16 storage: w_lm transposed, [V, ld_h], for the forward product (both operands stored along the contraction
+  // index is the fastest form of the bf16 GEMM); rewritten whenever the parameters are set
+  char* wlm_t = nullptr;
   int32_t* tok = nullptr;  // [max_inflight, T]
   int e_head = 0, e_count = 0;
   // head stash, one entry per kept micro-batch
@@ -250,7 +253,7 @@ hipError_t gemm(const mls_ends* s, int mode, const void* A, const void* B, void*
 }
 
 void release(mls_ends* s) {
-  void* p[] = {s->embed, s->gamma, s->wlm, s->tok, s->y, s->nrm, s->dlog, s->r, s->dn, s->partial, s->row_loss};
+  void* p[] = {s->embed, s->gamma, s->wlm, s->wlm_t, s->tok, s->y, s->nrm, s->dlog, s->r, s->dn, s->partial, s->row_loss};
   for (void* q : p)
     if (q) (void)hipFree(q);
   delete s;
@@ -302,6 +305,7 @@ int mls_ends_init(const mls_ends_config* cfg, uint64_t seed, void* hip_stream, m
   if ((e = alloc((void**)&s->embed, V * s->ld_h * s->es)) != hipSuccess ||
       (e = alloc((void**)&s->gamma, h * s->es)) != hipSuccess ||
       (e = alloc((void**)&s->wlm, h * s->ld_v * s->es)) != hipSuccess ||
+      (s->dt == mls::DT_BF16 && (e = alloc((void**)&s->wlm_t, V * s->ld_h * s->es)) != hipSuccess) ||
       (e = alloc((void**)&s->tok, nmb * T * 4)) != hipSuccess ||
       (e = alloc((void**)&s->y, nmb * s->mb_h)) != hipSuccess ||
       (e = alloc((void**)&s->nrm, nmb * s->mb_h)) != hipSuccess ||
@@ -320,6 +324,10 @@ int mls_ends_init(const mls_ends_config* cfg, uint64_t seed, void* hip_stream, m
       release(s);
       return fail_hip(e, "weight generator");
     }
+  if (s->wlm_t && (e = mls::transpose_bf16(s->wlm, s->ld_v, s->wlm_t, s->ld_h, c.hidden, c.vocab, s->st)) != hipSuccess) {
+    release(s);
+    return fail_hip(e, "transpose_bf16");
+  }
   if ((e = hipStreamSynchronize(s->st)) != hipSuccess) {
     release(s);
     return fail_hip(e, "hipStreamSynchronize");
@@ -399,7 +407,8 @@ static int head_forward(mls_ends* s, const void* y, const int32_t* targets, floa
   float* r = s->r + size_t(slot) * T;
   HIP_TRY(copy2d(s, ys, s->ld_h, y, h, T, h));
   HIP_TRY(mls::rmsnorm_fwd(s->dt, ys, s->ld_h, s->gamma, nr, s->ld_h, r, T, h, s->c.rms_eps, s->st));
-  HIP_TRY(gemm(s, mls::GEMM_NN, nr, s->wlm, dl, T, V, h, s->ld_h, s->ld_v, s->ld_v));
+  if (s->wlm_t) HIP_TRY(gemm(s, mls::GEMM_NT, nr, s->wlm_t, dl, T, V, h, s->ld_h, s->ld_h, s->ld_v));
+  else HIP_TRY(gemm(s, mls::GEMM_NN, nr, s->wlm, dl, T, V, h, s->ld_h, s->ld_v, s->ld_v));
   const float scale = loss_weight / (float)T;
   if (s->dt == mls::DT_BF16)
     hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(T), dim3(TH), 0, s->st, (bf16_t*)dl, s->ld_v, targets, V, scale, row_loss);
@@ -492,6 +501,7 @@ int mls_ends_set_params(mls_ends* s, const void* src) {
   PT t[3];
   param_tensors(s, t);
   for (auto& q : t) HIP_TRY(copy2d(s, q.ptr, q.ld, (const char*)src + q.off * s->es, q.cols, q.rows, q.cols));
+  if (s->wlm_t) HIP_TRY(mls::transpose_bf16(s->wlm, s->ld_v, s->wlm_t, s->ld_h, s->c.hidden, s->c.vocab, s->st));
   HIP_TRY(hipStreamSynchronize(s->st));
   return MLS_OK;
 }
