@@ -21,7 +21,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM bytes per GEMM launch (average over all gemm16_kernel and gemm_dma_kernel dispatches of a step), from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/stage_7b_4x4_hbm_traffic.txt:
-# (2.0 * 364203 KiB fetched + 1.0 * 84732 KiB written) * 1024.  Only valid for the default workload.
+# (2.0 * 364308 KiB fetched + 1.0 * 85181 KiB written) * 1024.  Only valid for the default workload.
 PROFILED_GEMM_TRAFFIC = {"7b": 8.33e8}
 
 
