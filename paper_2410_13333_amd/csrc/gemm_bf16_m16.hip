@@ -8,7 +8,7 @@
 // global->LDS requests; the compiler keeps volatile asm statements in program order).
 //
 // Shape: 4 wavefronts, one per SIMD, each owns 128x128 of the tile = 8x8 MFMA tiles = 64 accumulators of 4
-// registers, all in AGPRs.  k-tiles are 32 deep (one MFMA's depth), NS = 4 stages of 32 KiB in LDS, filled by
+// registers, all in AGPRs.  k-tiles are 32 deep (one MFMA's depth), NS = 4 stages (16 KiB of A, 16 KiB of B) in LDS, filled by
 // buffer_load_dwordx4 ... lds.  The fragments of a whole k-tile (8 of A, 8 of B, 16 bytes per lane each) live in
 // registers, in two sets: iteration t issues the MFMAs of tile t from one set while the LDS reads of tile t+1
 // fill the other, so no MFMA ever waits for LDS.  One barrier per iteration (after waiting for this wavefront's
