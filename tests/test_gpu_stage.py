@@ -82,6 +82,32 @@ def test_ragged_shape_with_fused_swiglu():
     _check(sh, [1, 3, 2], 1e-2, interleave=True)
 
 
+def test_set_params_reaches_every_copy_of_the_weights():
+    """The library keeps transposed copies of the weight matrices for its forward products: a stage whose parameters
+    were replaced by another stage's must give that stage's output and input gradient bit for bit."""
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = FUSED_RAGGED
+    a = mls.Stage.from_shape(sh, seed=1000)
+    b = mls.Stage.from_shape(sh, seed=4321)
+    x = to_device(synth.make_x(sh, 2000, 0)[0], "bf16")
+    dy = to_device(synth.make_dy(sh, 3000, 0)[0], "bf16")
+    out = []
+    for st in (a, b):
+        if st is b:
+            st.set_params(a.get_params())
+        y, dx = torch.empty_like(x), torch.empty_like(dy)
+        g = torch.zeros(st.grad_elems, dtype=torch.float32, device="cuda")
+        st.forward(x, sh.layers, y)
+        st.backward(dy.unsqueeze(0), g, 1, dx.unsqueeze(0))
+        torch.cuda.synchronize()
+        out.append((y, dx, g))
+    for u, v in zip(*out):
+        assert torch.equal(u, v)
+    a.close()
+    b.close()
+
+
 def test_head_dim_128_gqa_single_kv_head():
     _check(GQA128.with_(dtype="fp32"), [1, 1], 1e-4)
     _check(GQA128, [1, 1], 1e-2)
