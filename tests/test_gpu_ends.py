@@ -165,6 +165,33 @@ def test_ends_errors_and_stash_accounting():
     assert e.value.code == -1
 
 
+def test_ends_set_params_reaches_every_copy_of_the_weights():
+    """The head's forward product reads a transposed copy of w_lm: a handle whose parameters were replaced by another
+    handle's must give that handle's loss and gradients bit for bit."""
+    import torch
+    import paper_2410_13333_amd as mls
+    sh = TINY
+    a = mls.Ends.from_shape(sh, seed=1, max_inflight=1)
+    b = mls.Ends.from_shape(sh, seed=2, max_inflight=1)
+    b.set_params(a.get_params())
+    g = torch.Generator(device="cpu").manual_seed(3)
+    y = torch.randn(sh.tokens, sh.hidden, generator=g).to(a.tdtype).cuda()
+    tgt = torch.randint(0, sh.vocab, (sh.tokens,), generator=g, dtype=torch.int32).cuda()
+    out = []
+    for en in (a, b):
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        grads = torch.zeros(en.grad_elems, dtype=torch.float32, device="cuda")
+        dy = torch.empty((1, sh.micro_batch, sh.seq, sh.hidden), dtype=en.tdtype, device="cuda")
+        en.head_forward(y, tgt, 1.0, loss)
+        en.head_backward(grads, 1, dy)
+        torch.cuda.synchronize()
+        out.append((loss, grads, dy))
+        en.close()
+    for u, v in zip(*out):
+        assert torch.equal(u, v)
+    assert float(out[0][0]) > 0
+
+
 def test_whole_model_step_embedding_stage_head():
     """tokens -> embedding -> 2 decoder layers -> head -> loss and back, against the oracles chained the same way."""
     import torch
